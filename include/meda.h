@@ -1,0 +1,124 @@
+/*
+ * libmeda -- prefill-time KV-cache compression pass of MEDA (arXiv 2502.17599) for AMD MI355X
+ * (gfx950).  C ABI: plain pointers and sizes, no framework types.
+ *
+ * One call compresses the KV cache of one sequence over all layers:
+ *   1. attention of an observation window (the last W prompt positions) against every cached
+ *      key: causal softmax rows, cumulative attention score per key      (Section 3.3, A_s)
+ *   2. cross-modal attention entropy of every layer                       (Section 3.2, E_CM)
+ *   3. per-layer budgets S_l proportional to exp(E_CM), summing to the total budget
+ *                                                   (Section 3.2 allocation, Appendix A.3)
+ *   4. per kv head: text-prior boost, recent window M_l, Top-N_l          (Section 3.3, selection)
+ *   5. nearest conserved key by cosine similarity for every other key     (Section 3.3, matrix U)
+ *   6. average merging of keys and, with the same assignment, values      (Section 3.3, merging)
+ *   7. ragged per-layer compressed cache
+ *
+ * Memory: every data pointer is a DEVICE pointer owned by the caller; the library never
+ * allocates or frees device memory, never modifies the inputs and never synchronises the
+ * stream: work is enqueued on `hip_stream` and the call returns.  `params` is a host pointer.
+ * Errors: every function that can fail returns a meda_status; on an error detected on the host
+ * nothing has been launched and the outputs are untouched.
+ * Results are deterministic: the same inputs give bit-identical outputs on every run.
+ */
+#ifndef MEDA_H
+#define MEDA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MEDA_OK = 0,
+  MEDA_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, Hq % Hkv != 0, window > seq_len ...  */
+  MEDA_ERR_BUDGET = 2,      /* total_budget outside [L*min(W,T), L*T]                               */
+  MEDA_ERR_UNSUPPORTED = 3, /* head_dim / dtype / window / group size outside the built set         */
+  MEDA_ERR_WORKSPACE = 4,   /* workspace null, misaligned or smaller than meda_workspace_bytes()    */
+  MEDA_ERR_HIP = 5          /* a HIP call or kernel launch failed                                    */
+} meda_status;
+
+typedef enum { MEDA_F32 = 0, MEDA_BF16 = 1 } meda_dtype;
+
+/* flags */
+#define MEDA_FLAG_UNIFORM_BUDGET 1 /* skip the entropy softmax: S_l = B/L (+1 on the lowest layers)  */
+#define MEDA_FLAG_NO_MERGE 2       /* evict instead of merge: conserved rows are copied unchanged    */
+
+typedef struct {
+  int32_t n_layers;     /* L, 1..256                                                               */
+  int32_t n_q_heads;    /* Hq                                                                      */
+  int32_t n_kv_heads;   /* Hkv, Hq % Hkv == 0; query head h reads kv head h / (Hq/Hkv)             */
+  int32_t head_dim;     /* d: 64 or 128                                                            */
+  int32_t seq_len;      /* T: cached positions per layer                                           */
+  int32_t window;       /* W: rows of q_win = the last W positions, 1 <= W <= min(T, 128)          */
+  int64_t total_budget; /* B = sum_l S_l, kept positions per kv head summed over layers            */
+  int32_t recent_num;   /* M_l = max(min(W,S_l), floor(S_l*num/den)); 3/4 is the paper's 3:1 split */
+  int32_t recent_den;   /*   (Section 4.3); den > 0, 0 <= num <= den                               */
+  int32_t dtype;        /* meda_dtype of q_win, k, v, k_out, v_out                                 */
+  float softmax_scale;  /* 0 -> 1/sqrt(head_dim)                                                   */
+  int32_t flags;        /* MEDA_FLAG_*                                                             */
+} meda_params;
+
+/* Bytes of device scratch meda_compress needs for these parameters; 0 if they are invalid.       */
+size_t meda_workspace_bytes(const meda_params* params);
+
+/*
+ * The compression pass (Sections 3.2 and 3.3).
+ *
+ * Inputs (device, read-only):
+ *   q_win     [L][Hq][W][d]   queries of the last W positions (row i sits at position T-W+i)
+ *   k, v      [L][Hkv][T][d]  contiguous
+ *   modality  [T] uint8       0 = text position, 1 = vision position
+ * Outputs (device):
+ *   k_out, v_out   ragged: layer l holds [Hkv][S_l][d] starting at row layer_off[l]*Hkv; rows of
+ *                  a (layer, head) are in ascending original position; capacity B*Hkv*d elements
+ *   layer_len      [L]   int32  S_l
+ *   layer_off      [L+1] int64  prefix sums of S_l, layer_off[L] == B
+ *   entropy        [L]   double E_CM per layer; may be NULL
+ *   sel_idx        [B*Hkv] int32 original position of every output row, same ragged layout; may be NULL
+ *   merge_assign   [L][Hkv][T] int32 for every position the slot (row within its (layer, head)
+ *                  block) it was kept in or merged into; may be NULL
+ *   workspace      at least meda_workspace_bytes(params) bytes, 256-byte aligned
+ *   hip_stream     hipStream_t (NULL = the default stream)
+ * Calls that share a workspace must not overlap.
+ */
+meda_status meda_compress(const meda_params* params, const void* q_win, const void* k, const void* v,
+                          const uint8_t* modality, void* k_out, void* v_out, int32_t* layer_len,
+                          int64_t* layer_off, double* entropy, int32_t* sel_idx, int32_t* merge_assign,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Where an intermediate result lives inside the workspace after meda_compress (for tests and
+ * profiling tools).  Returns MEDA_ERR_INVALID_ARG for an unknown region or invalid params.
+ */
+typedef enum {
+  MEDA_REGION_COL_SCORES = 0, /* float [L][Hkv][T]: cumulative attention score A_s (Section 3.3)    */
+  MEDA_REGION_INV_NORM = 1,   /* float [L][Hkv][T]: 1/|k| of every key                              */
+  MEDA_REGION_ROW_STATS = 2,  /* float [L][Hq][Wp][4], Wp = W rounded up to 32: log2-domain row max,
+                                 1/Z over all visible keys, 1/Z over the row's cross-modal keys, 0   */
+  MEDA_REGION_ALLOC = 3,      /* int32 [L][4]: S_l, M_l, N_l, 0                                     */
+  MEDA_REGION_LESS_IDX = 4,   /* int32 ragged: layer l, head g at ((l*T - off[l])*Hkv + g*(T-S_l)):
+                                 positions that are not conserved, ascending                         */
+  MEDA_REGION_LESS_SLOT = 5   /* int32, same layout: slot each of them merges into                   */
+} meda_region;
+meda_status meda_workspace_region(const meda_params* params, int region, size_t* offset, size_t* bytes);
+
+/*
+ * Per-phase GPU timing.  While enabled, meda_compress records HIP events on its stream around
+ * every kernel; meda_profile_read waits for the recorded calls and returns, per phase, the
+ * summed kernel time in milliseconds and the number of calls since the last reset.
+ */
+#define MEDA_N_PHASES 8
+/* phases: 0 row statistics + key norms, 1 statistics combine, 2 column scores + entropy,
+ *         3 layer budgets, 4 selection, 5 similarity + argmax, 6 segment sort, 7 merge + write   */
+meda_status meda_profile_enable(int enable);
+meda_status meda_profile_read(double* phase_ms /* [MEDA_N_PHASES] */, int32_t* n_calls, int reset);
+const char* meda_phase_name(int phase);
+
+const char* meda_status_string(meda_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MEDA_H */

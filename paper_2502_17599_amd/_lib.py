@@ -1,0 +1,205 @@
+"""ctypes binding of libmeda.so: argument marshalling only, every step runs in the HIP kernels."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libmeda.so"
+
+EXPORTED_SYMBOLS = ("meda_workspace_bytes", "meda_compress", "meda_workspace_region",
+                    "meda_profile_enable", "meda_profile_read", "meda_phase_name", "meda_status_string")
+REGIONS = {"col_scores": 0, "inv_norm": 1, "row_stats": 2, "alloc": 3, "less_idx": 4, "less_slot": 5}
+N_PHASES = 8
+FLAG_UNIFORM_BUDGET = 1
+FLAG_NO_MERGE = 2
+_DTYPES = {torch.float32: 0, torch.bfloat16: 1}
+
+
+class MedaError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"libmeda: {message} (status {status})")
+        self.status = status
+
+
+class MedaParams(ctypes.Structure):
+    _fields_ = [("n_layers", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("seq_len", ctypes.c_int32), ("window", ctypes.c_int32),
+                ("total_budget", ctypes.c_int64), ("recent_num", ctypes.c_int32), ("recent_den", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("flags", ctypes.c_int32)]
+
+
+def library_path() -> str:
+    return os.path.join(_PKG_DIR, _LIB_NAME)
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libmeda.so from the package directory; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise MedaError(-1, f"{path} is missing: build it with `python -m paper_2502_17599_amd.build` "
+                            "(there is no fallback path)")
+    lib = ctypes.CDLL(path)
+    vp, pp = ctypes.c_void_p, ctypes.POINTER(MedaParams)
+    lib.meda_workspace_bytes.restype = ctypes.c_size_t
+    lib.meda_workspace_bytes.argtypes = [pp]
+    lib.meda_compress.restype = ctypes.c_int
+    lib.meda_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.meda_workspace_region.restype = ctypes.c_int
+    lib.meda_workspace_region.argtypes = [pp, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t),
+                                          ctypes.POINTER(ctypes.c_size_t)]
+    lib.meda_profile_enable.restype = ctypes.c_int
+    lib.meda_profile_enable.argtypes = [ctypes.c_int]
+    lib.meda_profile_read.restype = ctypes.c_int
+    lib.meda_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32), ctypes.c_int]
+    lib.meda_phase_name.restype = ctypes.c_char_p
+    lib.meda_phase_name.argtypes = [ctypes.c_int]
+    lib.meda_status_string.restype = ctypes.c_char_p
+    lib.meda_status_string.argtypes = [ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def meda_status_string(status: int) -> str:
+    return load_library().meda_status_string(status).decode()
+
+
+def meda_phase_name(phase: int) -> str:
+    return load_library().meda_phase_name(phase).decode()
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise MedaError(status, meda_status_string(status))
+
+
+def make_params(n_layers, n_q_heads, n_kv_heads, head_dim, seq_len, window, total_budget, dtype,
+                recent_num=3, recent_den=4, softmax_scale=0.0, flags=0) -> MedaParams:
+    code = _DTYPES.get(dtype, dtype if isinstance(dtype, int) else -1)
+    return MedaParams(n_layers, n_q_heads, n_kv_heads, head_dim, seq_len, window, total_budget,
+                      recent_num, recent_den, code, softmax_scale, flags)
+
+
+def meda_workspace_bytes(params: MedaParams) -> int:
+    return int(load_library().meda_workspace_bytes(ctypes.byref(params)))
+
+
+def meda_workspace_region(params: MedaParams, region) -> tuple:
+    """(byte offset, byte size) of an intermediate result inside the workspace."""
+    rid = REGIONS[region] if isinstance(region, str) else int(region)
+    off, size = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(load_library().meda_workspace_region(ctypes.byref(params), rid, ctypes.byref(off), ctypes.byref(size)))
+    return off.value, size.value
+
+
+def meda_profile_enable(enable: bool) -> None:
+    _check(load_library().meda_profile_enable(1 if enable else 0))
+
+
+def meda_profile_read(reset: bool = True):
+    """(list of per-phase summed milliseconds, number of calls) since the last reset."""
+    ms = (ctypes.c_double * N_PHASES)()
+    n = ctypes.c_int32(0)
+    _check(load_library().meda_profile_read(ms, ctypes.byref(n), 1 if reset else 0))
+    return [float(x) for x in ms], int(n.value)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+@dataclass
+class CompressedCache:
+    """Outputs of one call (device tensors; reading lengths on the host synchronises)."""
+    k_out: torch.Tensor           # [B*Hkv, d]
+    v_out: torch.Tensor
+    layer_len: torch.Tensor       # int32 [L]
+    layer_off: torch.Tensor       # int64 [L+1]
+    entropy: Optional[torch.Tensor]
+    sel_idx: Optional[torch.Tensor]
+    merge_assign: Optional[torch.Tensor]
+    n_kv_heads: int
+
+    def layer(self, l: int):
+        """(K, V[, positions]) of layer l as [Hkv, S_l, d] views."""
+        off = int(self.layer_off[l]); s = int(self.layer_len[l]); h = self.n_kv_heads
+        sl = slice(off * h, (off + s) * h)
+        d = self.k_out.shape[-1]
+        out = [self.k_out[sl].view(h, s, d), self.v_out[sl].view(h, s, d)]
+        if self.sel_idx is not None:
+            out.append(self.sel_idx[sl].view(h, s))
+        return tuple(out)
+
+
+class Compressor:
+    """Holds the parameters, the workspace and the output buffers for repeated calls of one shape."""
+
+    def __init__(self, params: MedaParams, device="cuda:0", want_entropy=True, want_sel_idx=True,
+                 want_merge_assign=False):
+        self.lib = load_library()
+        self.params = params
+        self.device = torch.device(device)
+        nbytes = meda_workspace_bytes(params)
+        if nbytes == 0:
+            # let the library say what is wrong with the parameters
+            off, size = ctypes.c_size_t(0), ctypes.c_size_t(0)
+            _check(self.lib.meda_workspace_region(ctypes.byref(params), 0, ctypes.byref(off), ctypes.byref(size)))
+            raise MedaError(1, "invalid parameters")
+        p = params
+        dt = {0: torch.float32, 1: torch.bfloat16}[p.dtype]
+        dev = self.device
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        rows = p.total_budget * p.n_kv_heads
+        self.k_out = torch.empty((rows, p.head_dim), dtype=dt, device=dev)
+        self.v_out = torch.empty((rows, p.head_dim), dtype=dt, device=dev)
+        self.layer_len = torch.empty(p.n_layers, dtype=torch.int32, device=dev)
+        self.layer_off = torch.empty(p.n_layers + 1, dtype=torch.int64, device=dev)
+        self.entropy = torch.empty(p.n_layers, dtype=torch.float64, device=dev) if want_entropy else None
+        self.sel_idx = torch.empty(rows, dtype=torch.int32, device=dev) if want_sel_idx else None
+        self.merge_assign = (torch.empty((p.n_layers, p.n_kv_heads, p.seq_len), dtype=torch.int32, device=dev)
+                             if want_merge_assign else None)
+
+    def region(self, name: str, dtype: torch.dtype) -> torch.Tensor:
+        off, size = meda_workspace_region(self.params, name)
+        return self.workspace[off:off + size].view(dtype)
+
+    def __call__(self, q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, modality: torch.Tensor,
+                 stream: Optional[torch.cuda.Stream] = None) -> CompressedCache:
+        p = self.params
+        dt = {0: torch.float32, 1: torch.bfloat16}[p.dtype]
+        for name, t, shape in (("q_win", q_win, (p.n_layers, p.n_q_heads, p.window, p.head_dim)),
+                               ("k", k, (p.n_layers, p.n_kv_heads, p.seq_len, p.head_dim)),
+                               ("v", v, (p.n_layers, p.n_kv_heads, p.seq_len, p.head_dim))):
+            if tuple(t.shape) != shape or t.dtype != dt or not t.is_contiguous() or t.device != self.device:
+                raise ValueError(f"{name}: expected contiguous {dt} tensor of shape {shape} on {self.device}")
+        if tuple(modality.shape) != (p.seq_len,) or modality.dtype != torch.uint8 or modality.device != self.device:
+            raise ValueError("modality: expected uint8 tensor of shape (seq_len,) on the same device")
+        s = stream if stream is not None else torch.cuda.current_stream(self.device)
+        st = self.lib.meda_compress(ctypes.byref(p), _ptr(q_win), _ptr(k), _ptr(v), _ptr(modality),
+                                    _ptr(self.k_out), _ptr(self.v_out), _ptr(self.layer_len), _ptr(self.layer_off),
+                                    _ptr(self.entropy), _ptr(self.sel_idx), _ptr(self.merge_assign),
+                                    _ptr(self.workspace), self.workspace.numel(), ctypes.c_void_p(s.cuda_stream))
+        _check(st)
+        return CompressedCache(self.k_out, self.v_out, self.layer_len, self.layer_off, self.entropy,
+                               self.sel_idx, self.merge_assign, p.n_kv_heads)
+
+
+def meda_compress(q_win, k, v, modality, total_budget, recent_num=3, recent_den=4, softmax_scale=0.0,
+                  flags=0, want_merge_assign=False, stream=None) -> CompressedCache:
+    """One-shot call: allocates workspace and outputs with torch, then runs the pass on the GPU."""
+    L, Hq, W, d = q_win.shape
+    _, Hkv, T, _ = k.shape
+    params = make_params(L, Hq, Hkv, d, T, W, int(total_budget), q_win.dtype, recent_num, recent_den,
+                         softmax_scale, flags)
+    comp = Compressor(params, q_win.device, want_merge_assign=want_merge_assign)
+    return comp(q_win, k, v, modality, stream)

@@ -1,0 +1,309 @@
+// Layer budgets from the cross-modal entropies (Section 3.2 allocation equation, Appendix A.3,
+// Section 4.3 for the recent : important split) and per-head token selection (Section 3.3: text
+// prior, recent window, Top-N).
+#include "device_utils.hpp"
+#include "plan.hpp"
+
+namespace meda {
+
+// ------------------------------------------------------------------------------------ allocation
+struct AllocArgs {
+  const double* ent_part;  // [L][NT][2]: minus sum p log p over text rows / vision rows, per column tile
+  const uint8_t* mask;
+  int32_t* alloc;          // [L][4]: S, M, N, 0
+  int64_t* off;            // [L+1]
+  int32_t* layer_len;      // user outputs
+  int64_t* layer_off;
+  double* entropy;         // may be null
+  int L, NT, T, W, num, den, flags;
+  long long B;
+};
+
+__device__ __forceinline__ double clampd(double v, double lo, double hi) { return fmin(fmax(v, lo), hi); }
+
+// One workgroup.  S_l = B * softmax_l(E_CM) when no bound is active; shares are kept inside
+// [min(W,T), T] by water-filling (x_l = clamp(lambda * w_l), sum x_l = B) and rounded by largest
+// remainder, so that sum_l S_l = B exactly.  All real arithmetic is double precision.
+__global__ void __launch_bounds__(256) allocate_kernel(AllocArgs a) {
+  __shared__ double E[kMaxLayers], w[kMaxLayers], x[kMaxLayers], frac[kMaxLayers];
+  __shared__ double kink[2 * kMaxLayers], filled[2 * kMaxLayers];
+  __shared__ int S[kMaxLayers], order[kMaxLayers];
+  __shared__ double s_lambda;
+  const int tid = threadIdx.x, L = a.L;
+  const double lo = (double)min(a.W, a.T), hi = (double)a.T, B = (double)a.B;
+
+  if (tid < L) {
+    int n_text = 0, n_vis = 0;
+    for (int i = 0; i < a.W; ++i) {
+      if (a.mask[a.T - a.W + i]) ++n_vis; else ++n_text;
+    }
+    double tv = 0.0, vt = 0.0;
+    const double* p = a.ent_part + (size_t)tid * a.NT * 2;
+    for (int t = 0; t < a.NT; ++t) {
+      tv += p[2 * t];
+      vt += p[2 * t + 1];
+    }
+    const double e = (n_text ? tv / n_text : 0.0) + (n_vis ? vt / n_vis : 0.0);
+    E[tid] = e;
+    if (a.entropy) a.entropy[tid] = e;
+  }
+  __syncthreads();
+
+  const bool uniform = (a.flags & MEDA_FLAG_UNIFORM_BUDGET) != 0;
+  if (tid < L) {
+    double emax = E[0];
+    for (int i = 1; i < L; ++i) emax = fmax(emax, E[i]);
+    w[tid] = uniform ? 1.0 : exp(E[tid] - emax);
+  }
+  __syncthreads();
+  // the filled amount sum_l clamp(lambda w_l) is piecewise linear in lambda with kinks at lo/w and hi/w
+  for (int i = tid; i < 2 * L; i += blockDim.x) {
+    const double b = (i < L) ? lo / w[i] : hi / w[i - L];
+    double f = 0.0;
+    for (int j = 0; j < L; ++j) f += clampd(b * w[j], lo, hi);
+    kink[i] = b;
+    filled[i] = f;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    double upper = -1.0, lower = 0.0;
+    for (int i = 0; i < 2 * L; ++i) {
+      if (filled[i] >= B) {
+        if (upper < 0.0 || kink[i] < upper) upper = kink[i];
+      } else if (kink[i] > lower) {
+        lower = kink[i];
+      }
+    }
+    const double mid = 0.5 * (lower + upper);
+    double wsum = 0.0;
+    int n_lo = 0, n_hi = 0;
+    for (int j = 0; j < L; ++j) {
+      const double v = mid * w[j];
+      if (v <= lo) ++n_lo;
+      else if (v >= hi) ++n_hi;
+      else wsum += w[j];
+    }
+    s_lambda = (wsum > 0.0) ? (B - lo * n_lo - hi * n_hi) / wsum : upper;
+  }
+  __syncthreads();
+  if (tid < L) {
+    double xv = clampd(s_lambda * w[tid], lo, hi);
+    if (a.B == (long long)L * a.T) xv = hi;
+    if (a.B == (long long)L * min(a.W, a.T)) xv = lo;
+    const double fl = floor(xv);
+    x[tid] = xv;
+    frac[tid] = xv - fl;
+    S[tid] = (int)clampd(fl, lo, hi);
+  }
+  __syncthreads();
+  if (tid < L) {
+    int rank = 0;
+    const double f = frac[tid];
+    for (int j = 0; j < L; ++j) rank += (frac[j] > f || (frac[j] == f && j < tid)) ? 1 : 0;
+    order[rank] = tid;  // decreasing fractional part, ties towards the lower layer
+  }
+  __syncthreads();
+  if (tid == 0) {
+    long long sum = 0;
+    for (int j = 0; j < L; ++j) sum += S[j];
+    long long rest = a.B - sum;
+    for (int round = 0; round < 4 && rest > 0; ++round)
+      for (int r = 0; r < L && rest > 0; ++r) {
+        const int lyr = order[r];
+        if (S[lyr] < a.T) { ++S[lyr]; --rest; }
+      }
+    for (int round = 0; round < 4 && rest < 0; ++round)  // only reachable through rounding fuzz
+      for (int r = L - 1; r >= 0 && rest < 0; --r) {
+        const int lyr = order[r];
+        if (S[lyr] > min(a.W, a.T)) { --S[lyr]; ++rest; }
+      }
+    long long o = 0;
+    for (int j = 0; j < L; ++j) {
+      const int s = S[j];
+      const int m = max(min(a.W, s), (int)(((long long)s * a.num) / a.den));
+      a.alloc[4 * j + 0] = s;
+      a.alloc[4 * j + 1] = m;
+      a.alloc[4 * j + 2] = s - m;
+      a.alloc[4 * j + 3] = 0;
+      a.off[j] = o;
+      a.layer_len[j] = s;
+      a.layer_off[j] = o;
+      o += s;
+    }
+    a.off[L] = o;
+    a.layer_off[L] = o;
+  }
+}
+
+// ------------------------------------------------------------------------------------- selection
+struct SelectArgs {
+  const float* col_scores;  // [L][Hkv][T]
+  const uint8_t* mask;
+  const int32_t* alloc;
+  const int64_t* off;
+  int32_t* sel_idx;         // ragged [B*Hkv]
+  int32_t* sel_idx_user;    // may be null
+  int32_t* less_idx;        // ragged [(L*T-B)*Hkv]
+  int32_t* merge_assign;    // may be null, [L][Hkv][T]
+  int L, Hkv, T;
+};
+
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / 64;
+
+// Exclusive rank of a one-bit flag over the workgroup (ballots inside a wave, wave totals in LDS).
+// `totals` has 2*kSelWaves ints; `slot` selects which half.  Returns rank; *block_total = number of set flags.
+__device__ __forceinline__ int flag_rank_in_wave(bool flag, int lane, int* wave_total) {
+  const unsigned long long b = __ballot(flag);
+  *wave_total = __popcll(b);
+  return __popcll(b & ((1ull << lane) - 1ull));
+}
+
+// grid (Hkv, L).  Adding max(A_s) to every text score puts all text candidates above all vision
+// candidates and keeps the order inside each modality, so the Top-N of the boosted scores is:
+// all text candidates plus the best vision ones if N exceeds the number of text candidates, else
+// the best N text candidates.  The order inside one modality is found exactly on the unboosted
+// fp32 scores (no bits are lost to the addition) with a 4 x 8-bit radix select on their bit
+// patterns (scores are >= 0, so the unsigned order of the bits is the order of the values); equal
+// scores go to the smaller position.
+__global__ void __launch_bounds__(kSelThreads) select_kernel(SelectArgs a) {
+  __shared__ int hist[256];
+  __shared__ int wtot[2][kSelWaves];
+  __shared__ int s_red[kSelWaves];
+  __shared__ unsigned s_prefix;
+  __shared__ int s_remaining;
+
+  const int g = blockIdx.x, l = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int T = a.T;
+  const int S = a.alloc[4 * l + 0], M = a.alloc[4 * l + 1], N = a.alloc[4 * l + 2];
+  const int ncand = T - M;
+  const long long off_l = a.off[l];
+  const float* scores = a.col_scores + (size_t)(l * a.Hkv + g) * T;
+  const size_t c_base = (size_t)off_l * a.Hkv + (size_t)g * S;
+  const size_t less_base = ((size_t)l * T - (size_t)off_l) * a.Hkv + (size_t)g * (T - S);
+
+  // number of text candidates
+  int cnt = 0;
+  for (int j = tid; j < ncand; j += kSelThreads) cnt += (a.mask[j] == 0) ? 1 : 0;
+  cnt = wave_sum(cnt);
+  if (lane == 0) s_red[wave] = cnt;
+  __syncthreads();
+  int n_text = 0;
+  for (int i = 0; i < kSelWaves; ++i) n_text += s_red[i];
+
+  const bool pick_text = N <= n_text;            // class in which the cut falls
+  const int K = pick_text ? N : N - n_text;      // how many of that class are taken
+  const bool other_taken = !pick_text;           // vision cut: every text candidate is taken
+  const uint8_t cls = pick_text ? 0 : 1;
+
+  unsigned threshold = 0xffffffffu;
+  int ties_taken = 0;
+  if (K > 0) {
+    if (tid == 0) { s_prefix = 0u; s_remaining = K; }
+    unsigned prefix_mask = 0u;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      if (tid < 256) hist[tid] = 0;
+      __syncthreads();
+      const unsigned prefix = s_prefix;
+      for (int j = tid; j < ncand; j += kSelThreads) {
+        if ((a.mask[j] != 0) == (cls != 0)) {
+          const unsigned key = __float_as_uint(scores[j]);
+          if ((key & prefix_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+        }
+      }
+      __syncthreads();
+      if (tid == 0) {
+        int remaining = s_remaining, cum = 0, digit = 0;
+        for (int b = 255; b >= 0; --b) {
+          if (cum + hist[b] >= remaining) { digit = b; break; }
+          cum += hist[b];
+        }
+        s_remaining = remaining - cum;
+        s_prefix = prefix | ((unsigned)digit << shift);
+      }
+      prefix_mask |= 255u << shift;
+      __syncthreads();
+    }
+    threshold = s_prefix;
+    ties_taken = s_remaining;
+  }
+
+  // ordered output: conserved positions ascending, the rest ascending
+  int run_c = 0, run_tie = 0;
+  for (int base = 0; base < T; base += kSelThreads) {
+    const int j = base + tid;
+    const bool valid = j < T;
+    bool in_cls = false, is_tie = false, above = false;
+    if (valid && j < ncand) {
+      in_cls = (a.mask[j] != 0) == (cls != 0);
+      if (in_cls) {
+        const unsigned key = __float_as_uint(scores[j]);
+        above = key > threshold;
+        is_tie = key == threshold;
+      }
+    }
+    int wt_tie, wt_sel;
+    const int tie_in_wave = flag_rank_in_wave(is_tie, lane, &wt_tie);
+    if (lane == 0) wtot[0][wave] = wt_tie;
+    __syncthreads();
+    int tie_rank = run_tie + tie_in_wave, tie_total = 0;
+    for (int i = 0; i < kSelWaves; ++i) {
+      const int v = wtot[0][i];
+      tie_rank += (i < wave) ? v : 0;
+      tie_total += v;
+    }
+    const bool sel = valid && (j >= ncand || (in_cls ? (above || (is_tie && tie_rank < ties_taken)) : other_taken));
+    const int sel_in_wave = flag_rank_in_wave(sel, lane, &wt_sel);
+    if (lane == 0) wtot[1][wave] = wt_sel;
+    __syncthreads();
+    int pos_c = run_c + sel_in_wave, sel_total = 0;
+    for (int i = 0; i < kSelWaves; ++i) {
+      const int v = wtot[1][i];
+      pos_c += (i < wave) ? v : 0;
+      sel_total += v;
+    }
+    if (sel) {
+      a.sel_idx[c_base + pos_c] = j;
+      if (a.sel_idx_user) a.sel_idx_user[c_base + pos_c] = j;
+      if (a.merge_assign) a.merge_assign[(size_t)(l * a.Hkv + g) * T + j] = pos_c;
+    } else if (valid) {
+      a.less_idx[less_base + (j - pos_c)] = j;
+    }
+    run_c += sel_total;
+    run_tie += tie_total;
+  }
+}
+
+// ------------------------------------------------------------------------------------------ launch
+
+hipError_t launch_allocate(const Plan& p, const Buffers& b, hipStream_t s) {
+  AllocArgs a;
+  a.ent_part = reinterpret_cast<const double*>(b.ws + p.off_ent_part);
+  a.mask = b.mask;
+  a.alloc = reinterpret_cast<int32_t*>(b.ws + p.off_alloc);
+  a.off = reinterpret_cast<int64_t*>(b.ws + p.off_layer_off);
+  a.layer_len = b.layer_len;
+  a.layer_off = b.layer_off;
+  a.entropy = b.entropy;
+  a.L = p.L; a.NT = p.NT; a.T = p.T; a.W = p.W; a.num = p.num; a.den = p.den; a.flags = p.flags;
+  a.B = p.B;
+  hipLaunchKernelGGL(allocate_kernel, dim3(1), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const Plan& p, const Buffers& b, hipStream_t s) {
+  SelectArgs a;
+  a.col_scores = reinterpret_cast<const float*>(b.ws + p.off_col_scores);
+  a.mask = b.mask;
+  a.alloc = reinterpret_cast<const int32_t*>(b.ws + p.off_alloc);
+  a.off = reinterpret_cast<const int64_t*>(b.ws + p.off_layer_off);
+  a.sel_idx = reinterpret_cast<int32_t*>(b.ws + p.off_sel_idx);
+  a.sel_idx_user = b.sel_idx_user;
+  a.less_idx = reinterpret_cast<int32_t*>(b.ws + p.off_less_idx);
+  a.merge_assign = b.merge_assign;
+  a.L = p.L; a.Hkv = p.Hkv; a.T = p.T;
+  hipLaunchKernelGGL(select_kernel, dim3(p.Hkv, p.L), dim3(kSelThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace meda

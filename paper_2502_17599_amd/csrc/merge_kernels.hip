@@ -1,0 +1,430 @@
+// Merging phases (Section 3.3, "Multimodal KV Pair Merging"): cosine similarity between every
+// less-important key and every conserved key with a fused row argmax, a stable sort of the
+// less-important positions by the slot they merge into, and the average merge of keys and values
+// written straight into the ragged output.
+#include "device_utils.hpp"
+#include "plan.hpp"
+
+namespace meda {
+
+struct MergeArgs {
+  const char* k;
+  const char* v;
+  char* k_out;
+  char* v_out;
+  const float* inv_norm;    // [L][Hkv][T]
+  const int32_t* alloc;     // [L][4]
+  const int64_t* off;       // [L+1]
+  const int32_t* sel_idx;   // ragged conserved positions
+  const int32_t* less_idx;  // ragged less-important positions (ascending)
+  int32_t* less_slot;       // ragged: slot each of them merges into
+  int32_t* sort_key[2];     // ping-pong buffers of the segment sort
+  int32_t* sort_val[2];
+  int32_t* seg_start;       // ragged [B*Hkv + L*Hkv]: (S_l + 1) entries per (layer, head)
+  int32_t* merge_assign;    // may be null
+  int L, Hkv, T, flags;
+  long long total_slots;    // B * Hkv
+};
+
+__device__ __forceinline__ size_t less_base_of(int l, int g, int T, int Hkv, long long off_l, int S) {
+  return ((size_t)l * T - (size_t)off_l) * Hkv + (size_t)g * (T - S);
+}
+
+// number of 4-bit passes the segment sort needs for slots in [0, S)
+__device__ __forceinline__ int sort_passes(int S) {
+  const int nbits = (S > 1) ? (32 - __clz(S - 1)) : 1;
+  return (nbits + 3) / 4;
+}
+
+// ------------------------------------------------------------------------ similarity + argmax
+// grid (ceil(T / 256), Hkv, L); 4 waves x 64 less-important rows.  Each wave keeps its rows as two
+// A-operand fragments in registers for the whole kernel and streams the conserved keys of its
+// (layer, head) through LDS in tiles of 64 slots.  u_ij = (k_i . k_j) / (|k_i| |k_j|): the raw keys
+// are multiplied (bf16 products are exact in the fp32 accumulator), the column factor 1/|k_j| is
+// applied to the accumulator, and the positive row factor 1/|k_i| is dropped because it cannot
+// change the argmax over j.  Ties go to the lower slot.
+template <typename T, int D>
+__global__ void __launch_bounds__(kSimWaves * 64) similarity_argmax_kernel(MergeArgs a) {
+  using TL = Tile<T, D>;
+  __shared__ __align__(16) char ctile[kSimSlotTile * TL::kStride];
+  __shared__ float cinv[kSimSlotTile];
+
+  const int g = blockIdx.y, l = blockIdx.z;
+  const int S = a.alloc[4 * l];
+  const int n_less = a.T - S;
+  const int row_base = blockIdx.x * kSimRows;
+  if (row_base >= n_less) return;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, kg = lane >> 5;
+  const long long off_l = a.off[l];
+  const int32_t* cidx = a.sel_idx + (size_t)off_l * a.Hkv + (size_t)g * S;
+  const size_t lbase = less_base_of(l, g, a.T, a.Hkv, off_l, S);
+  const int32_t* less = a.less_idx + lbase;
+  const char* kbase = a.k + (size_t)(l * a.Hkv + g) * a.T * TL::kRowBytes;
+  const float* invn = a.inv_norm + (size_t)(l * a.Hkv + g) * a.T;
+
+  Frag<T, D> af[2];
+  const int r0 = row_base + wave * kSimRowsPerWave;
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    const int ri = r0 + s * 32 + n;
+    if (ri < n_less)
+      frag_load(af[s], kbase + (size_t)less[ri] * TL::kRowBytes, kg);
+    else
+      frag_zero(af[s]);
+  }
+  float best[2][16];
+  int bidx[2][16];
+#pragma unroll
+  for (int s = 0; s < 2; ++s)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      best[s][r] = -INFINITY;
+      bidx[s][r] = 0;
+    }
+
+  constexpr int CPR = TL::kChunksPerRow;
+  for (int s0 = 0; s0 < S; s0 += kSimSlotTile) {
+    __syncthreads();
+    const int nslots = min(kSimSlotTile, S - s0);
+    for (int c = tid; c < kSimSlotTile * CPR; c += kSimWaves * 64) {
+      const int row = c / CPR, cc = c - row * CPR;
+      uint4 val = make_uint4(0, 0, 0, 0);
+      if (row < nslots)
+        val = *reinterpret_cast<const uint4*>(kbase + (size_t)cidx[s0 + row] * TL::kRowBytes + cc * 16);
+      *reinterpret_cast<uint4*>(ctile + row * TL::kStride + cc * 16) = val;
+    }
+    if (tid < kSimSlotTile) cinv[tid] = (tid < nslots) ? invn[cidx[s0 + tid]] : 0.f;
+    __syncthreads();
+    const bool tail = nslots < kSimSlotTile;
+#pragma unroll
+    for (int cb = 0; cb < kSimSlotTile / 32; ++cb) {
+      if (s0 + cb * 32 < S) {
+        Frag<T, D> bf;
+        frag_load(bf, ctile + (cb * 32 + n) * TL::kStride, kg);
+        const float iv = cinv[cb * 32 + n];
+        const int slot = s0 + cb * 32 + n;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+          f32x16_t acc = acc_zero();
+          mma<T, D>(acc, af[s], bf);
+          if (!tail) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const float u = acc[r] * iv;
+              const bool better = u > best[s][r];
+              best[s][r] = better ? u : best[s][r];
+              bidx[s][r] = better ? slot : bidx[s][r];
+            }
+          } else {
+            const bool slot_ok = slot < S;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const float u = acc[r] * iv;
+              const bool better = slot_ok && u > best[s][r];
+              best[s][r] = better ? u : best[s][r];
+              bidx[s][r] = better ? slot : bidx[s][r];
+            }
+          }
+        }
+      }
+    }
+  }
+
+  // argmax over the 32 lanes that hold different slots of the same row; ties -> lower slot
+#pragma unroll
+  for (int s = 0; s < 2; ++s)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float bv = best[s][r];
+      int bi = bidx[s][r];
+#pragma unroll
+      for (int o = 1; o < 32; o <<= 1) {
+        const float ov = __shfl_xor(bv, o, kWave);
+        const int oi = __shfl_xor(bi, o, kWave);
+        const bool take = ov > bv || (ov == bv && oi < bi);
+        bv = take ? ov : bv;
+        bi = take ? oi : bi;
+      }
+      if (n == r) {
+        const int ri = r0 + s * 32 + acc_row(r, kg);
+        if (ri < n_less) {
+          a.less_slot[lbase + ri] = bi;
+          if (a.merge_assign) a.merge_assign[(size_t)(l * a.Hkv + g) * a.T + less[ri]] = bi;
+        }
+      }
+    }
+}
+
+// ------------------------------------------------------------------------------- segment sort
+// grid (Hkv, L); 1024 threads.  Stable least-significant-digit radix sort (4 bits per pass) of the
+// pairs (slot, position) of one (layer, head) by slot; positions enter ascending, so every slot's
+// members come out ascending and the merge adds them in one fixed order.  Then seg_start[s] = first
+// sorted index whose slot is >= s.
+constexpr int kSortThreads = 1024;
+constexpr int kSortWaves = kSortThreads / 64;
+
+__global__ void __launch_bounds__(kSortThreads) segment_sort_kernel(MergeArgs a) {
+  __shared__ int base[16];
+  __shared__ int wcnt[kSortWaves][16];
+
+  const int g = blockIdx.x, l = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int S = a.alloc[4 * l];
+  const int n = a.T - S;
+  const long long off_l = a.off[l];
+  const size_t lbase = less_base_of(l, g, a.T, a.Hkv, off_l, S);
+  const unsigned long long lt_mask = (1ull << lane) - 1ull;
+  const int passes = sort_passes(S);
+
+  const int32_t* in_key = a.less_slot + lbase;
+  const int32_t* in_val = a.less_idx + lbase;
+  for (int p = 0; p < passes; ++p) {
+    int32_t* out_key = a.sort_key[p & 1] + lbase;
+    int32_t* out_val = a.sort_val[p & 1] + lbase;
+    const int shift = 4 * p;
+    if (tid < 16) base[tid] = 0;
+    __syncthreads();
+    // digit histogram
+    int mine[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) mine[q] = 0;
+    for (int t0 = 0; t0 < n; t0 += kSortThreads) {
+      const int i = t0 + tid;
+      const int dgt = (i < n) ? ((in_key[i] >> shift) & 15) : 16;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) mine[q] += __popcll(__ballot(dgt == q));
+    }
+    if (lane == 0) {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) atomicAdd(&base[q], mine[q]);
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int run = 0;
+      for (int q = 0; q < 16; ++q) {
+        const int c = base[q];
+        base[q] = run;
+        run += c;
+      }
+    }
+    __syncthreads();
+    // stable scatter, 1024 elements at a time in input order
+    for (int t0 = 0; t0 < n; t0 += kSortThreads) {
+      const int i = t0 + tid;
+      const bool valid = i < n;
+      const int key = valid ? in_key[i] : 0;
+      const int val = valid ? in_val[i] : 0;
+      const int dgt = valid ? ((key >> shift) & 15) : 16;
+      int my_rank = 0;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const unsigned long long b = __ballot(dgt == q);
+        if (dgt == q) my_rank = __popcll(b & lt_mask);
+        if (lane == 0) wcnt[wave][q] = __popcll(b);
+      }
+      __syncthreads();
+      if (valid) {
+        int pos = base[dgt] + my_rank;
+        for (int w2 = 0; w2 < wave; ++w2) pos += wcnt[w2][dgt];
+        out_key[pos] = key;
+        out_val[pos] = val;
+      }
+      __syncthreads();
+      if (tid < 16) {
+        int tot = 0;
+        for (int w2 = 0; w2 < kSortWaves; ++w2) tot += wcnt[w2][tid];
+        base[tid] += tot;
+      }
+      __syncthreads();
+    }
+    in_key = out_key;
+    in_val = out_val;
+  }
+
+  // segment starts from the sorted slots
+  int32_t* seg = a.seg_start + (size_t)off_l * a.Hkv + (size_t)g * S + (size_t)(l * a.Hkv + g);
+  for (int i = tid; i < n; i += kSortThreads) {
+    const int kcur = in_key[i];
+    const int kprev = (i > 0) ? in_key[i - 1] : -1;
+    for (int s = kprev + 1; s <= kcur; ++s) seg[s] = i;
+  }
+  const int klast = (n > 0) ? in_key[n - 1] : -1;
+  for (int s = klast + 1 + tid; s <= S; s += kSortThreads) seg[s] = n;
+}
+
+// ------------------------------------------------------------------------------ merge + write
+// One wave per output row (layer, head, slot).  k_j <- (k_j + sum_{i in N_j} k_i) / (|N_j| + 1) and
+// the same for the values (Section 3.3, average merging).  A lane owns one 16-byte piece of a row,
+// so 64 lanes read 1024 bytes = several rows per step; sums are kept in fp64 (exact for the value
+// ranges of a KV cache, hence independent of the summation order) and rounded once to the
+// storage type.
+template <typename T>
+struct OutConv;
+template <>
+struct OutConv<bf16_t> {
+  static constexpr int kElems = 8;
+  static __device__ __forceinline__ void unpack(const uint4& v, double* out) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      out[2 * i] = (double)__uint_as_float(w[i] << 16);
+      out[2 * i + 1] = (double)__uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ uint4 pack(const double* in) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = double_to_bf16_bits(in[2 * i]) | (double_to_bf16_bits(in[2 * i + 1]) << 16);
+    return make_uint4(w[0], w[1], w[2], w[3]);
+  }
+};
+template <>
+struct OutConv<float> {
+  static constexpr int kElems = 4;
+  static __device__ __forceinline__ void unpack(const uint4& v, double* out) {
+    out[0] = (double)__uint_as_float(v.x);
+    out[1] = (double)__uint_as_float(v.y);
+    out[2] = (double)__uint_as_float(v.z);
+    out[3] = (double)__uint_as_float(v.w);
+  }
+  static __device__ __forceinline__ uint4 pack(const double* in) {
+    return make_uint4(__float_as_uint(__double2float_rn(in[0])), __float_as_uint(__double2float_rn(in[1])),
+                      __float_as_uint(__double2float_rn(in[2])), __float_as_uint(__double2float_rn(in[3])));
+  }
+};
+
+template <typename T, int D>
+__global__ void __launch_bounds__(256) merge_write_kernel(MergeArgs a) {
+  using TL = Tile<T, D>;
+  using CV = OutConv<T>;
+  constexpr int LPR = TL::kChunksPerRow;  // lanes per row
+  constexpr int MS = 64 / LPR;            // rows per step
+  constexpr int E = CV::kElems;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const long long w = (long long)blockIdx.x * 4 + wave;
+  if (w >= a.total_slots) return;
+  // layer of this output row: largest l with off[l]*Hkv <= w
+  int lo_l = 0, hi_l = a.L;
+  while (hi_l - lo_l > 1) {
+    const int mid = (lo_l + hi_l) >> 1;
+    if (a.off[mid] * a.Hkv <= w) lo_l = mid; else hi_l = mid;
+  }
+  const int l = lo_l;
+  const long long off_l = a.off[l];
+  const int S = a.alloc[4 * l];
+  const long long rem = w - off_l * a.Hkv;
+  const int g = (int)(rem / S), s = (int)(rem - (long long)g * S);
+  const int pos = a.sel_idx[w];
+  int m_lo = 0, m_hi = 0;
+  const int32_t* members = nullptr;
+  if (!(a.flags & MEDA_FLAG_NO_MERGE) && a.T > S) {
+    const int32_t* seg = a.seg_start + w + (l * a.Hkv + g);
+    m_lo = seg[0];
+    m_hi = seg[1];
+    const int fin = (sort_passes(S) - 1) & 1;
+    members = a.sort_val[fin] + less_base_of(l, g, a.T, a.Hkv, off_l, S);
+  }
+  const int n_rows = m_hi - m_lo + 1;  // the conserved row and its members
+  const int sub = lane / LPR, cc = lane - sub * LPR;
+  const size_t head_base = (size_t)(l * a.Hkv + g) * a.T * TL::kRowBytes;
+  const char* kb = a.k + head_base + cc * 16;
+  const char* vb = a.v + head_base + cc * 16;
+
+  double ak[E], av[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    ak[i] = 0.0;
+    av[i] = 0.0;
+  }
+  for (int e = sub; e < n_rows; e += MS) {
+    const int row = (e == 0) ? pos : members[m_lo + e - 1];
+    const uint4 kv = *reinterpret_cast<const uint4*>(kb + (size_t)row * TL::kRowBytes);
+    const uint4 vv = *reinterpret_cast<const uint4*>(vb + (size_t)row * TL::kRowBytes);
+    double tk[E], tv[E];
+    CV::unpack(kv, tk);
+    CV::unpack(vv, tv);
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      ak[i] += tk[i];
+      av[i] += tv[i];
+    }
+  }
+#pragma unroll
+  for (int o = LPR; o < 64; o <<= 1) {
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      ak[i] += __shfl_xor(ak[i], o, kWave);
+      av[i] += __shfl_xor(av[i], o, kWave);
+    }
+  }
+  if (sub == 0) {
+    const double denom = (double)n_rows;
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      ak[i] /= denom;
+      av[i] /= denom;
+    }
+    *reinterpret_cast<uint4*>(a.k_out + (size_t)w * TL::kRowBytes + cc * 16) = CV::pack(ak);
+    *reinterpret_cast<uint4*>(a.v_out + (size_t)w * TL::kRowBytes + cc * 16) = CV::pack(av);
+  }
+}
+
+// ------------------------------------------------------------------------------------------ launch
+
+static MergeArgs make_args(const Plan& p, const Buffers& b) {
+  MergeArgs a;
+  a.k = static_cast<const char*>(b.k);
+  a.v = static_cast<const char*>(b.v);
+  a.k_out = static_cast<char*>(b.k_out);
+  a.v_out = static_cast<char*>(b.v_out);
+  a.inv_norm = reinterpret_cast<const float*>(b.ws + p.off_inv_norm);
+  a.alloc = reinterpret_cast<const int32_t*>(b.ws + p.off_alloc);
+  a.off = reinterpret_cast<const int64_t*>(b.ws + p.off_layer_off);
+  a.sel_idx = reinterpret_cast<const int32_t*>(b.ws + p.off_sel_idx);
+  a.less_idx = reinterpret_cast<const int32_t*>(b.ws + p.off_less_idx);
+  a.less_slot = reinterpret_cast<int32_t*>(b.ws + p.off_less_slot);
+  a.sort_key[0] = reinterpret_cast<int32_t*>(b.ws + p.off_sort_a);
+  a.sort_val[0] = reinterpret_cast<int32_t*>(b.ws + p.off_sort_b);
+  a.sort_key[1] = reinterpret_cast<int32_t*>(b.ws + p.off_sort_c);
+  a.sort_val[1] = reinterpret_cast<int32_t*>(b.ws + p.off_sort_d);
+  a.seg_start = reinterpret_cast<int32_t*>(b.ws + p.off_seg_start);
+  a.merge_assign = b.merge_assign;
+  a.L = p.L; a.Hkv = p.Hkv; a.T = p.T; a.flags = p.flags;
+  a.total_slots = (long long)p.B * p.Hkv;
+  return a;
+}
+
+template <typename T, int D>
+static hipError_t launch_sim_t(const Plan& p, const MergeArgs& a, hipStream_t s) {
+  dim3 grid((p.T + kSimRows - 1) / kSimRows, p.Hkv, p.L);
+  hipLaunchKernelGGL((similarity_argmax_kernel<T, D>), grid, dim3(kSimWaves * 64), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_similarity(const Plan& p, const Buffers& b, hipStream_t s) {
+  const MergeArgs a = make_args(p, b);
+  if (p.dtype == MEDA_BF16) return p.d == 128 ? launch_sim_t<bf16_t, 128>(p, a, s) : launch_sim_t<bf16_t, 64>(p, a, s);
+  return p.d == 128 ? launch_sim_t<float, 128>(p, a, s) : launch_sim_t<float, 64>(p, a, s);
+}
+
+hipError_t launch_segment_sort(const Plan& p, const Buffers& b, hipStream_t s) {
+  const MergeArgs a = make_args(p, b);
+  hipLaunchKernelGGL(segment_sort_kernel, dim3(p.Hkv, p.L), dim3(kSortThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+template <typename T, int D>
+static hipError_t launch_merge_t(const Plan& p, const MergeArgs& a, hipStream_t s) {
+  const long long blocks = (a.total_slots + 3) / 4;
+  hipLaunchKernelGGL((merge_write_kernel<T, D>), dim3((unsigned)blocks), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_write(const Plan& p, const Buffers& b, hipStream_t s) {
+  const MergeArgs a = make_args(p, b);
+  if (p.dtype == MEDA_BF16) return p.d == 128 ? launch_merge_t<bf16_t, 128>(p, a, s) : launch_merge_t<bf16_t, 64>(p, a, s);
+  return p.d == 128 ? launch_merge_t<float, 128>(p, a, s) : launch_merge_t<float, 64>(p, a, s);
+}
+
+}  // namespace meda

@@ -1,0 +1,62 @@
+// Host-side launch plan: everything derived from meda_params (tile counts, workspace regions) and
+// the entry points of the kernel translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/meda.h"
+
+namespace meda {
+
+constexpr int kScoreTile = 128;   // key columns per LDS tile in the two scoring passes
+constexpr int kSimRowsPerWave = 64;
+constexpr int kSimWaves = 4;
+constexpr int kSimRows = kSimRowsPerWave * kSimWaves;  // less-important rows per workgroup
+constexpr int kSimSlotTile = 64;                       // conserved slots staged in LDS per step
+constexpr int kMaxLayers = 256;
+
+struct Plan {
+  // problem
+  int L, Hq, Hkv, G, d, T, W;
+  int64_t B;
+  int num, den, dtype, flags;
+  float scale_log2;  // softmax scale times log2(e): logits are kept in the base-2 domain
+  int elt;           // bytes per element
+  // scoring
+  int RB, Wp;        // 32-row blocks of the window, padded window
+  int NQ, NCG, CS;   // pass A: (head, row block) pairs per wave, wave groups, column split
+  int CH, NCH, NPART;  // pass A: columns per chunk, chunks, partial statistics per row
+  int NT;            // pass B: column tiles
+  // workspace regions (byte offsets)
+  size_t off_stats_part, off_stats, off_inv_norm, off_col_scores, off_ent_part, off_alloc, off_layer_off,
+      off_sel_idx, off_less_idx, off_less_slot, off_sort_a, off_sort_b, off_sort_c, off_sort_d, off_seg_start, total_bytes;
+  size_t n_less_total;  // (L*T - B) * Hkv
+};
+
+meda_status make_plan(const meda_params* p, Plan* plan);
+
+struct Buffers {
+  const void *q, *k, *v;
+  const uint8_t* mask;
+  void *k_out, *v_out;
+  int32_t* layer_len;
+  int64_t* layer_off;
+  double* entropy;
+  int32_t* sel_idx_user;
+  int32_t* merge_assign;
+  char* ws;
+};
+
+// kernel launchers (one per phase); each returns the hipError_t of its launch
+hipError_t launch_score_stats(const Plan&, const Buffers&, hipStream_t);
+hipError_t launch_stats_combine(const Plan&, const Buffers&, hipStream_t);
+hipError_t launch_score_accum(const Plan&, const Buffers&, hipStream_t);
+hipError_t launch_allocate(const Plan&, const Buffers&, hipStream_t);
+hipError_t launch_select(const Plan&, const Buffers&, hipStream_t);
+hipError_t launch_similarity(const Plan&, const Buffers&, hipStream_t);
+hipError_t launch_segment_sort(const Plan&, const Buffers&, hipStream_t);
+hipError_t launch_merge_write(const Plan&, const Buffers&, hipStream_t);
+
+}  // namespace meda

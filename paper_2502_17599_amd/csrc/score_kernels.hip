@@ -1,0 +1,388 @@
+// Scoring phases of the compression pass (Section 3.2: cross-modal attention entropy; Section 3.3:
+// cumulative attention score).  The softmax normalisers of a window row are needed before any of its
+// probabilities can be added to a column sum or to the head-averaged cross-modal matrix, so the keys
+// are visited twice:
+//   pass A  score_stats_kernel   row maxima and normalisers (all keys / vision keys / text keys),
+//                                split over column chunks; also 1/|k| of every key (used by the merge)
+//           stats_combine_kernel merges the chunk partials of every row
+//   pass B  score_accum_kernel   recomputes the logits, adds normalised probabilities into the column
+//                                scores A_s and into the head-averaged cross-modal matrix, whose row
+//                                entropies are reduced per tile
+// Logits are kept in the base-2 domain: t = (q.k) * scale * log2(e), probabilities are exp2(t - max).
+#include "device_utils.hpp"
+#include "plan.hpp"
+
+namespace meda {
+
+struct ScoreArgs {
+  const char* q;
+  const char* k;
+  const uint8_t* mask;
+  float4* stats_part;  // [L][Hq][Wp][NPART] (max, Z_vision, Z_text, -)
+  float4* stats;       // [L][Hq][Wp]        (max, 1/Z_all, coef for vision columns, coef for text columns)
+  float* inv_norm;     // [L][Hkv][T]
+  float* col_scores;   // [L][Hkv][T]
+  double* ent_part;    // [L][NT][2]
+  int L, Hq, Hkv, G, T, W, RB, Wp;
+  int NCG, CS, CH, NPART, NT;
+  float c;             // scale * log2(e)
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ------------------------------------------------------------------------------------------ pass A
+// grid (NCH, Hkv, L); NCG*CS waves.  Wave (cg, cs) keeps NQ query fragments ((head of the group, row
+// block) pairs cg*NQ .. cg*NQ+NQ-1) in registers and visits the 32-key blocks sb = cs, cs+CS, ... of
+// every tile of its chunk.  The product is taken with the keys as operand A and the queries as
+// operand B, so a lane owns one query row and 16 keys per block: the running (max, Z_vision, Z_text)
+// of the row live in three registers per fragment and need no cross-lane traffic until the end.
+template <typename T, int D, int NQ>
+__global__ void __launch_bounds__(512) score_stats_kernel(ScoreArgs a) {
+  using TL = Tile<T, D>;
+  extern __shared__ __align__(16) char smem[];
+  char* ktile = smem;
+  uint8_t* lmask = reinterpret_cast<uint8_t*>(smem + kScoreTile * TL::kStride);
+
+  const int ch = blockIdx.x, g = blockIdx.y, l = blockIdx.z;
+  const int tid = threadIdx.x, nthr = blockDim.x;
+  const int wave = tid >> 6, lane = tid & 63, n = lane & 31, kg = lane >> 5;
+  const int cgi = wave % a.NCG, cs = wave / a.NCG;
+  const int n_combos = a.G * a.RB;
+
+  Frag<T, D> qf[NQ];
+  float m[NQ], zv[NQ], zt[NQ];
+  int qrow[NQ], qhead[NQ];
+  int nvalid = 0;
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) {
+    const int cidx = cgi * NQ + q;
+    m[q] = kNegBig;
+    zv[q] = 0.f;
+    zt[q] = 0.f;
+    qrow[q] = 0;
+    qhead[q] = 0;
+    frag_zero(qf[q]);
+    if (cidx < n_combos) {
+      nvalid = q + 1;
+      const int hg = cidx / a.RB, rb = cidx - hg * a.RB;
+      qhead[q] = g * a.G + hg;
+      qrow[q] = rb * 32 + n;
+      if (qrow[q] < a.W)
+        frag_load(qf[q], a.q + ((size_t)(l * a.Hq + qhead[q]) * a.W + qrow[q]) * TL::kRowBytes, kg);
+    }
+  }
+
+  const int jbeg = ch * a.CH;
+  const int jend = min(a.T, jbeg + a.CH);
+  const char* kbase = a.k + (size_t)(l * a.Hkv + g) * a.T * TL::kRowBytes;
+  float* invn_out = a.inv_norm + (size_t)(l * a.Hkv + g) * a.T;
+
+  for (int j0 = jbeg; j0 < jend; j0 += kScoreTile) {
+    __syncthreads();
+    const int rows_valid = min(kScoreTile, a.T - j0);
+    tile_load_contiguous<T, D>(ktile, kbase + (size_t)j0 * TL::kRowBytes, kScoreTile, rows_valid, tid, nthr);
+    if (tid < kScoreTile) lmask[tid] = (j0 + tid < a.T) ? a.mask[j0 + tid] : 0;
+    __syncthreads();
+
+    // 1/|k| of the tile's keys: two threads per row
+    for (int row = tid >> 1; row < kScoreTile; row += nthr >> 1) {
+      const uint4* p = reinterpret_cast<const uint4*>(ktile + row * TL::kStride + (tid & 1) * TL::kHalfBytes);
+      float ss = 0.f;
+#pragma unroll
+      for (int i = 0; i < TL::kFragChunks; ++i) ss += chunk_sumsq<T>(p[i]);
+      ss += __shfl_xor(ss, 1, kWave);
+      if ((tid & 1) == 0 && row < rows_valid) invn_out[j0 + row] = 1.0f / fmaxf(sqrtf(ss), 1e-30f);
+    }
+
+    for (int sb = cs; sb < kScoreTile / 32; sb += a.CS) {
+      const int jb = j0 + sb * 32;
+      if (jb >= a.T) break;
+      Frag<T, D> kf;
+      frag_load(kf, ktile + (sb * 32 + n) * TL::kStride, kg);
+      const uint32_t mword = (uint32_t)__ballot(lmask[sb * 32 + n] != 0);
+      const bool full = jb + 31 <= a.T - a.W;  // every key of the block is visible to every window row
+      const bool uniform = full && (mword == 0u || mword == 0xffffffffu);
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) {
+        if (q < nvalid) {
+          f32x16_t acc = acc_zero();
+          mma<T, D>(acc, kf, qf[q]);
+          float t[16];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) t[r] = acc[r] * a.c;
+          if (!full) {
+            const int p = a.T - a.W + qrow[q];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int j = jb + acc_row(r, kg);
+              t[r] = (j < a.T && j <= p) ? t[r] : kNegBig;
+            }
+          }
+          float bm = t[0];
+#pragma unroll
+          for (int r = 1; r < 16; ++r) bm = fmaxf(bm, t[r]);
+          const float mn = fmaxf(m[q], bm);
+          const float sc = fast_exp2(m[q] - mn);
+          zv[q] *= sc;
+          zt[q] *= sc;
+          m[q] = mn;
+          if (uniform) {
+            float s = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s += fast_exp2(t[r] - mn);
+            if (mword)
+              zv[q] += s;
+            else
+              zt[q] += s;
+          } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const float e = (t[r] > 0.5f * kNegBig) ? fast_exp2(t[r] - mn) : 0.f;
+              const bool vis = (mword >> acc_row(r, kg)) & 1u;
+              zv[q] += vis ? e : 0.f;
+              zt[q] += vis ? 0.f : e;
+            }
+          }
+        }
+      }
+    }
+  }
+
+  // the two lane groups hold disjoint keys of the same query row: merge them, then store the partial
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) {
+    if (q < nvalid) {
+      const float mo = __shfl_xor(m[q], 32, kWave);
+      const float zvo = __shfl_xor(zv[q], 32, kWave);
+      const float zto = __shfl_xor(zt[q], 32, kWave);
+      const float M = fmaxf(m[q], mo);
+      const float f1 = fast_exp2(m[q] - M), f2 = fast_exp2(mo - M);
+      if (kg == 0 && qrow[q] < a.W) {
+        const size_t row_id = (size_t)(l * a.Hq + qhead[q]) * a.Wp + qrow[q];
+        a.stats_part[row_id * a.NPART + ch * a.CS + cs] =
+            make_float4(M, zv[q] * f1 + zvo * f2, zt[q] * f1 + zto * f2, 0.f);
+      }
+    }
+  }
+}
+
+// One thread per (layer, query head, padded window row): merge the NPART partials.
+__global__ void __launch_bounds__(256) stats_combine_kernel(ScoreArgs a) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  const int total = a.L * a.Hq * a.Wp;
+  if (idx >= total) return;
+  const int row = idx % a.Wp;
+  if (row >= a.W) {
+    a.stats[idx] = make_float4(0.f, 0.f, 0.f, 0.f);
+    return;
+  }
+  const float4* part = a.stats_part + (size_t)idx * a.NPART;
+  float M = kNegBig;
+  for (int i = 0; i < a.NPART; ++i) M = fmaxf(M, part[i].x);
+  float zv = 0.f, zt = 0.f;
+  for (int i = 0; i < a.NPART; ++i) {
+    const float4 p = part[i];
+    const float f = fast_exp2(p.x - M);
+    zv = fmaf(p.y, f, zv);
+    zt = fmaf(p.z, f, zt);
+  }
+  const bool row_is_vision = a.mask[a.T - a.W + row] != 0;
+  const float coef_v = (!row_is_vision && zv > 0.f) ? 1.0f / zv : 0.f;  // text row: attends to vision columns
+  const float coef_t = (row_is_vision && zt > 0.f) ? 1.0f / zt : 0.f;   // vision row: attends to text columns
+  a.stats[idx] = make_float4(M, 1.0f / (zv + zt), coef_v, coef_t);
+}
+
+// ------------------------------------------------------------------------------------------ pass B
+// grid (NT, L); 4 waves; wave w owns the 32 key columns w*32.. of the tile, a lane owns one column.
+// The workgroup walks over all kv heads and, inside, the query heads of the group, so the
+// head-averaged cross-modal probabilities of its W x 128 patch accumulate in registers (same
+// accumulator layout for every head) and the entropy terms p log p can be taken once at the end.
+template <typename T, int D, int RB>
+__global__ void __launch_bounds__(256) score_accum_kernel(ScoreArgs a) {
+  using TL = Tile<T, D>;
+  extern __shared__ __align__(16) char smem[];
+  char* ktile = smem;
+  char* qtile = ktile + kScoreTile * TL::kStride;
+  float* st_m = reinterpret_cast<float*>(qtile + RB * 32 * TL::kStride);
+  float* st_rz = st_m + RB * 32;
+  float* st_cv = st_rz + RB * 32;
+  float* st_ct = st_cv + RB * 32;
+  double* red = reinterpret_cast<double*>(st_ct + RB * 32);  // [4][2]
+
+  const int tile = blockIdx.x, l = blockIdx.y;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, kg = lane >> 5;
+  const int j0 = tile * kScoreTile;
+  const int j = j0 + wave * 32 + n;  // this lane's key column
+  const bool col_ok = j < a.T;
+  const bool col_is_vision = col_ok && a.mask[j] != 0;
+  const float* st_coef = col_is_vision ? st_cv : st_ct;
+  const bool full = j0 + kScoreTile - 1 <= a.T - a.W;
+  const int rows_valid = min(kScoreTile, a.T - j0);
+  const int Wp = RB * 32;
+
+  float pbar[RB][16];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) pbar[rb][r] = 0.f;
+
+  for (int g = 0; g < a.Hkv; ++g) {
+    Frag<T, D> kf;
+    float colsum = 0.f;
+    for (int hg = 0; hg < a.G; ++hg) {
+      const int h = g * a.G + hg;
+      __syncthreads();  // the previous head's tiles are no longer read
+      if (hg == 0)
+        tile_load_contiguous<T, D>(ktile, a.k + ((size_t)(l * a.Hkv + g) * a.T + j0) * TL::kRowBytes, kScoreTile,
+                                   rows_valid, tid, 256);
+      tile_load_contiguous<T, D>(qtile, a.q + (size_t)(l * a.Hq + h) * a.W * TL::kRowBytes, Wp, a.W, tid, 256);
+      if (tid < Wp) {
+        const float4 s = a.stats[(size_t)(l * a.Hq + h) * a.Wp + tid];
+        st_m[tid] = s.x;
+        st_rz[tid] = s.y;
+        st_cv[tid] = s.z;
+        st_ct[tid] = s.w;
+      }
+      __syncthreads();
+      if (hg == 0) frag_load(kf, ktile + (wave * 32 + n) * TL::kStride, kg);
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        Frag<T, D> qf;
+        frag_load(qf, qtile + (rb * 32 + n) * TL::kStride, kg);
+        f32x16_t acc = acc_zero();
+        mma<T, D>(acc, qf, kf);
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int row0 = rb * 32 + r4 * 8 + kg * 4;  // rows of acc[r4*4 .. r4*4+3]
+          const float4 m4 = *reinterpret_cast<const float4*>(st_m + row0);
+          const float4 z4 = *reinterpret_cast<const float4*>(st_rz + row0);
+          const float4 c4 = *reinterpret_cast<const float4*>(st_coef + row0);
+          const float mm[4] = {m4.x, m4.y, m4.z, m4.w};
+          const float zz[4] = {z4.x, z4.y, z4.z, z4.w};
+          const float cc[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            float e = fast_exp2(fmaf(acc[r4 * 4 + i], a.c, -mm[i]));
+            if (!full) {
+              const int row = row0 + i;
+              e = (col_ok && row < a.W && j <= a.T - a.W + row) ? e : 0.f;
+            }
+            colsum = fmaf(e, zz[i], colsum);
+            pbar[rb][r4 * 4 + i] = fmaf(e, cc[i], pbar[rb][r4 * 4 + i]);
+          }
+        }
+      }
+    }
+    colsum += __shfl_xor(colsum, 32, kWave);
+    if (kg == 0 && col_ok) a.col_scores[(size_t)(l * a.Hkv + g) * a.T + j] = colsum;
+  }
+
+  // entropy terms of the head-averaged cross-modal probabilities.  A vision column only receives
+  // probability from text rows (text -> vision direction) and a text column only from vision rows.
+  const float inv_heads = 1.0f / (float)a.Hq;
+  float s = 0.f;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float p = pbar[rb][r] * inv_heads;
+      s += (p > 0.f) ? p * __logf(p) : 0.f;
+    }
+  const double tv = wave_sum(col_is_vision ? (double)s : 0.0);
+  const double vt = wave_sum((col_ok && !col_is_vision) ? (double)s : 0.0);
+  __syncthreads();
+  if (lane == 0) {
+    red[wave * 2 + 0] = tv;
+    red[wave * 2 + 1] = vt;
+  }
+  __syncthreads();
+  if (tid < 2) {
+    const double sum = red[tid] + red[2 + tid] + red[4 + tid] + red[6 + tid];
+    a.ent_part[((size_t)l * a.NT + tile) * 2 + tid] = -sum;
+  }
+}
+
+// ------------------------------------------------------------------------------------------ launch
+
+static ScoreArgs make_args(const Plan& p, const Buffers& b) {
+  ScoreArgs a;
+  a.q = static_cast<const char*>(b.q);
+  a.k = static_cast<const char*>(b.k);
+  a.mask = b.mask;
+  a.stats_part = reinterpret_cast<float4*>(b.ws + p.off_stats_part);
+  a.stats = reinterpret_cast<float4*>(b.ws + p.off_stats);
+  a.inv_norm = reinterpret_cast<float*>(b.ws + p.off_inv_norm);
+  a.col_scores = reinterpret_cast<float*>(b.ws + p.off_col_scores);
+  a.ent_part = reinterpret_cast<double*>(b.ws + p.off_ent_part);
+  a.L = p.L; a.Hq = p.Hq; a.Hkv = p.Hkv; a.G = p.G; a.T = p.T; a.W = p.W; a.RB = p.RB; a.Wp = p.Wp;
+  a.NCG = p.NCG; a.CS = p.CS; a.CH = p.CH; a.NPART = p.NPART; a.NT = p.NT;
+  a.c = p.scale_log2;
+  return a;
+}
+
+template <typename T, int D, int NQ>
+static hipError_t launch_stats_t(const Plan& p, const ScoreArgs& a, hipStream_t s) {
+  const size_t lds = (size_t)kScoreTile * Tile<T, D>::kStride + kScoreTile;
+  auto kern = score_stats_kernel<T, D, NQ>;
+  if (lds > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  dim3 grid(p.NCH, p.Hkv, p.L), block(p.NCG * p.CS * 64);
+  hipLaunchKernelGGL(kern, grid, block, lds, s, a);
+  return hipGetLastError();
+}
+
+template <typename T, int D>
+static hipError_t launch_stats_d(const Plan& p, const ScoreArgs& a, hipStream_t s) {
+  switch (p.NQ) {
+    case 1: return launch_stats_t<T, D, 1>(p, a, s);
+    case 2: return launch_stats_t<T, D, 2>(p, a, s);
+    default: return launch_stats_t<T, D, 4>(p, a, s);
+  }
+}
+
+hipError_t launch_score_stats(const Plan& p, const Buffers& b, hipStream_t s) {
+  const ScoreArgs a = make_args(p, b);
+  if (p.dtype == MEDA_BF16) return p.d == 128 ? launch_stats_d<bf16_t, 128>(p, a, s) : launch_stats_d<bf16_t, 64>(p, a, s);
+  return p.d == 128 ? launch_stats_d<float, 128>(p, a, s) : launch_stats_d<float, 64>(p, a, s);
+}
+
+hipError_t launch_stats_combine(const Plan& p, const Buffers& b, hipStream_t s) {
+  const ScoreArgs a = make_args(p, b);
+  const int total = p.L * p.Hq * p.Wp;
+  hipLaunchKernelGGL(stats_combine_kernel, dim3((total + 255) / 256), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+template <typename T, int D, int RB>
+static hipError_t launch_accum_t(const Plan& p, const ScoreArgs& a, hipStream_t s) {
+  const size_t lds = (size_t)(kScoreTile + RB * 32) * Tile<T, D>::kStride + 4 * RB * 32 * sizeof(float) + 64;
+  auto kern = score_accum_kernel<T, D, RB>;
+  if (lds > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(kern, dim3(p.NT, p.L), dim3(256), lds, s, a);
+  return hipGetLastError();
+}
+
+template <typename T, int D>
+static hipError_t launch_accum_d(const Plan& p, const ScoreArgs& a, hipStream_t s) {
+  switch (p.RB) {
+    case 1: return launch_accum_t<T, D, 1>(p, a, s);
+    case 2: return launch_accum_t<T, D, 2>(p, a, s);
+    case 3: return launch_accum_t<T, D, 3>(p, a, s);
+    default: return launch_accum_t<T, D, 4>(p, a, s);
+  }
+}
+
+hipError_t launch_score_accum(const Plan& p, const Buffers& b, hipStream_t s) {
+  const ScoreArgs a = make_args(p, b);
+  if (p.dtype == MEDA_BF16) return p.d == 128 ? launch_accum_d<bf16_t, 128>(p, a, s) : launch_accum_d<bf16_t, 64>(p, a, s);
+  return p.d == 128 ? launch_accum_d<float, 128>(p, a, s) : launch_accum_d<float, 64>(p, a, s);
+}
+
+}  // namespace meda

@@ -1,0 +1,100 @@
+"""The C-ABI library loads, exports every symbol include/meda.h declares, and rejects bad arguments on
+the host before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+import paper_2502_17599_amd as pkg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(pkg.library_path()):
+        from paper_2502_17599_amd.build import build_library
+        build_library()
+    return pkg.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "meda.h")).read()
+    declared = set(re.findall(r"\b(meda_[a-z_]+)\s*\(", header))
+    assert declared == set(pkg.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_params_struct_matches_header_layout():
+    assert ctypes.sizeof(pkg.MedaParams) == 56
+    assert pkg.MedaParams.total_budget.offset == 24 and pkg.MedaParams.flags.offset == 48
+
+
+def _params(**kw):
+    base = dict(n_layers=4, n_q_heads=8, n_kv_heads=2, head_dim=128, seq_len=1000, window=32,
+                total_budget=4 * 250, dtype=torch.bfloat16)
+    base.update(kw)
+    return pkg.make_params(**base)
+
+
+def test_workspace_bytes_valid_and_invalid(lib):
+    assert pkg.meda_workspace_bytes(_params()) > 0
+    assert pkg.meda_workspace_bytes(_params()) % 256 == 0
+    for bad in (dict(n_layers=0), dict(n_q_heads=7), dict(head_dim=96), dict(window=0), dict(window=2000),
+                dict(total_budget=4 * 31), dict(total_budget=4 * 1000 + 1), dict(recent_den=0),
+                dict(recent_num=5, recent_den=4), dict(dtype=7), dict(window=129, seq_len=4096, total_budget=4 * 500),
+                dict(n_layers=300, total_budget=300 * 250)):
+        assert pkg.meda_workspace_bytes(_params(**bad)) == 0, bad
+
+
+def _status(lib, params, ptrs, ws_bytes):
+    args = [ctypes.byref(params)] + [ctypes.c_void_p(p) for p in ptrs[:12]] + [ctypes.c_size_t(ws_bytes), None]
+    return lib.meda_compress(*args)
+
+
+def test_compress_rejects_bad_arguments_before_launching(lib):
+    p = _params()
+    need = pkg.meda_workspace_bytes(p)
+    fake = 0x10000  # never dereferenced: every case below fails validation on the host
+    good = [fake] * 8 + [0, 0, 0] + [fake]          # entropy, sel_idx, merge_assign may be null
+    assert _status(lib, _params(total_budget=1), good, need) == 2          # MEDA_ERR_BUDGET
+    assert _status(lib, _params(head_dim=80), good, need) == 3             # MEDA_ERR_UNSUPPORTED
+    assert _status(lib, _params(n_q_heads=3), good, need) == 1             # MEDA_ERR_INVALID_ARG
+    for i in range(8):                                                      # required pointers
+        ptrs = list(good); ptrs[i] = 0
+        assert _status(lib, p, ptrs, need) == 1, i
+    ptrs = list(good); ptrs[11] = 0
+    assert _status(lib, p, ptrs, need) == 4                                 # MEDA_ERR_WORKSPACE: null
+    assert _status(lib, p, good, need - 1) == 4                             # too small
+    ptrs = list(good); ptrs[11] = fake + 8
+    assert _status(lib, p, ptrs, need) == 4                                 # misaligned
+    ptrs = list(good); ptrs[1] = fake + 4
+    assert _status(lib, p, ptrs, need) == 1                                 # k not 16-byte aligned
+
+
+def test_status_strings_and_regions(lib):
+    assert pkg.meda_status_string(0) == "ok"
+    assert "budget" in pkg.meda_status_string(2)
+    p = _params()
+    total = pkg.meda_workspace_bytes(p)
+    seen = []
+    for name in pkg.REGIONS:
+        off, size = pkg.meda_workspace_region(p, name)
+        assert off % 256 == 0 and off + size <= total
+        seen.append((off, off + size))
+    seen.sort()
+    assert all(a[1] <= b[0] for a, b in zip(seen, seen[1:]))
+    with pytest.raises(pkg.MedaError):
+        pkg.meda_workspace_region(p, 99)
+    assert [pkg.meda_phase_name(i) for i in range(pkg.N_PHASES)][0] == "score_stats"
+
+
+def test_binding_refuses_without_library(monkeypatch, tmp_path):
+    import paper_2502_17599_amd._lib as L
+    monkeypatch.setattr(L, "_lib", None)
+    monkeypatch.setattr(L, "_PKG_DIR", str(tmp_path))
+    with pytest.raises(pkg.MedaError):
+        L.load_library()

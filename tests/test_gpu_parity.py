@@ -1,0 +1,93 @@
+"""HIP path vs fp64 oracle, element by element, through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+from workloads import generate, get_workload, variant
+
+from parity import check_all, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(wl, **kw):
+    print(f"\n[case] {wl.name}: L={wl.n_layers} Hq={wl.n_q_heads} Hkv={wl.n_kv_heads} d={wl.head_dim} "
+          f"T={wl.seq_len} W={wl.window} B={wl.total_budget} {wl.dtype} seed={wl.seed}", flush=True)
+    data = generate(wl)
+    comp, gpu = run_gpu(wl, data)
+    return check_all(wl, data, gpu, **kw)
+
+
+TINY = get_workload("tiny")
+VT_LAYOUT = (("t", 64, -1), ("v", 256, 0), ("v", 256, 1), ("v", 256, 2), ("t", 160, -1), ("v", 16, 2), ("t", 16, -1))
+
+
+def test_tiny_fp32():
+    stats = _case(TINY)
+    assert stats["budgets_strictly_equal"]
+
+
+def test_tiny_window_with_vision_rows():
+    _case(variant(TINY, name="tiny_vt", layout=VT_LAYOUT))
+
+
+def test_tiny_full_budget_is_identity():
+    wl = variant(TINY, name="tiny_identity", total_budget=TINY.n_layers * TINY.seq_len)
+    data = generate(wl)
+    comp, gpu = run_gpu(wl, data)
+    assert np.all(gpu["S"] == wl.seq_len)
+    k = data["k"].to(torch.float64).numpy().reshape(-1, wl.head_dim)
+    v = data["v"].to(torch.float64).numpy().reshape(-1, wl.head_dim)
+    assert np.array_equal(gpu["k_out"], k) and np.array_equal(gpu["v_out"], v)
+    check_all(wl, data, gpu)
+
+
+def test_tiny_floor_budget():
+    _case(variant(TINY, name="tiny_floor", total_budget=TINY.n_layers * TINY.window))
+
+
+def test_tiny_equal_temperatures_split_evenly():
+    wl = variant(TINY, name="tiny_equal_tau", tau_lo=1.5, tau_hi=1.5, n_layers=3, total_budget=700)
+    _case(wl)
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_small_bf16_gqa_ragged(seed):
+    # several column tiles and a ragged tail (T = 1000 is no multiple of 128), grouped heads, 3 layers
+    layout = (("t", 40, -1), ("v", 300, 0), ("t", 30, -1), ("v", 300, 1), ("t", 10, -1), ("v", 200, 2), ("t", 120, -1))
+    wl = variant(TINY, name=f"small_bf16_s{seed}", n_layers=3, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                 dtype="bf16", layout=layout, window=32, total_budget=3 * 230, seed=seed)
+    assert wl.seq_len == 1000
+    _case(wl)
+
+
+def test_small_bf16_window_48_mixed_rows():
+    # window that is no multiple of 32 and holds vision rows; group size 3
+    layout = (("t", 33, -1), ("v", 400, 0), ("t", 77, -1), ("v", 350, 1), ("t", 100, -1), ("v", 20, 1), ("t", 20, -1))
+    wl = variant(TINY, name="small_w48", n_layers=2, n_q_heads=6, n_kv_heads=2, head_dim=128, dtype="bf16",
+                 layout=layout, window=48, total_budget=2 * 300, seed=3)
+    _case(wl)
+
+
+def test_small_fp32_d128_and_bf16_d64():
+    layout = (("t", 50, -1), ("v", 500, 0), ("t", 150, -1))
+    _case(variant(TINY, name="f32_d128", n_layers=2, n_q_heads=2, n_kv_heads=2, head_dim=128, dtype="f32",
+                  layout=layout, window=32, total_budget=2 * 200, seed=4))
+    _case(variant(TINY, name="bf16_d64", n_layers=2, n_q_heads=4, n_kv_heads=1, head_dim=64, dtype="bf16",
+                  layout=layout, window=64, total_budget=2 * 200, seed=5))
+
+
+def test_window_equals_sequence():
+    layout = (("v", 40, 0), ("t", 24, -1))
+    _case(variant(TINY, name="w_eq_t", n_layers=2, n_q_heads=2, n_kv_heads=1, layout=layout, window=64,
+                  total_budget=2 * 64, seed=6))
+
+
+def test_deterministic_across_runs():
+    wl = variant(TINY, name="det", n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=128, dtype="bf16",
+                 layout=(("t", 60, -1), ("v", 700, 0), ("t", 140, -1)), total_budget=2 * 180, seed=7)
+    data = generate(wl)
+    _, a = run_gpu(wl, data)
+    _, b = run_gpu(wl, data)
+    for key in ("k_out", "v_out", "sel_idx", "merge_assign", "entropy", "col_scores"):
+        assert np.array_equal(a[key], b[key]), key
