@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Throughput of the whole compression pass on one MI355X.
+
+One step = one meda_compress call: every phase of the pass over all layers and heads of one synthetic
+sequence whose inputs are already resident in HBM.  Prints one JSON line with the whole-job throughput
+(context tokens compressed per second), the roofline figures of the dominant kernel (HIP-event time of
+that kernel measured inside the timed region) and the CPU oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+PHASE_BOUND = {"score_stats": "hbm", "score_accum": "hbm", "similarity": "mfma", "merge_write": "hbm",
+               "select": "hbm", "segment_sort": "hbm", "stats_combine": "hbm", "allocate": "hbm"}
+
+
+def algorithmic_work(wl, budgets):
+    """Per launch: bytes the method itself must move (hbm phases) or flops it must do (similarity)."""
+    L, Hkv, T, d = wl.n_layers, wl.n_kv_heads, wl.seq_len, wl.head_dim
+    e = 2 if wl.dtype == "bf16" else 4
+    k_bytes = L * Hkv * T * d * e
+    out_rows = int(sum(budgets)) * Hkv
+    less = [(T - s) * Hkv for s in budgets]
+    return {
+        "score_stats": k_bytes,                                    # every key once
+        "score_accum": k_bytes,                                    # every key once
+        "similarity": sum(2.0 * (T - s) * s * d * Hkv for s in budgets),   # flops
+        "merge_write": 2 * k_bytes + 2 * out_rows * d * e,         # every K and V row once + the output
+        "select": L * Hkv * T * 4,
+        "segment_sort": sum(less) * 8,
+        "stats_combine": 0,
+        "allocate": 0,
+    }
+
+
+def cpu_baseline(wl, seconds_target=20.0):
+    """The fp64 oracle on a bounded sample: the first n layers of the same workload with the budget
+    scaled to n layers, n chosen from a one-layer probe so the run takes roughly ``seconds_target``."""
+    import numpy as np
+    from oracle import meda_oracle as O
+    from workloads import generate, variant
+    from workloads.gen import to_float64
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+
+    def run(n_layers):
+        sub = variant(wl, n_layers=n_layers, total_budget=(wl.total_budget * n_layers) // wl.n_layers)
+        data = generate(sub, threads=min(8, n_layers))
+        q, k, v = to_float64(data["q"]), to_float64(data["k"]), to_float64(data["v"])
+        t0 = time.perf_counter()
+        O.meda_compress(q, k, v, data["mask"].numpy(), sub.total_budget, sub.window, sub.dtype,
+                        recent_num=sub.recent_num, recent_den=sub.recent_den)
+        return time.perf_counter() - t0
+
+    t1 = run(1)
+    n = int(max(1, min(wl.n_layers, seconds_target // max(t1, 1e-3))))
+    t = run(n) if n > 1 else t1
+    per_pass = t * wl.n_layers / n
+    return {"value": wl.seq_len / per_pass, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {n} of {wl.n_layers} layers (all heads, budget scaled to {n} layers), "
+                      f"{t:.1f} s, scaled by {wl.n_layers}/{n}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llava7b_multi_image")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-phase-events", action="store_true",
+                    help="do not record per-kernel HIP events inside the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU only (one MI355X holds all layers and heads); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2502_17599_amd as pkg
+    from workloads import generate, get_workload
+
+    wl = get_workload(args.workload)
+    dev = torch.device("cuda:0")
+    data = generate(wl, threads=16)
+    q, k, v, mask = (data[n].to(dev) for n in ("q", "k", "v", "mask"))
+    params = pkg.make_params(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.seq_len, wl.window,
+                             wl.total_budget, q.dtype, wl.recent_num, wl.recent_den)
+    comp = pkg.Compressor(params, dev, want_entropy=True, want_sel_idx=True, want_merge_assign=False)
+    stream = torch.cuda.current_stream(dev)
+
+    for _ in range(args.warmup):
+        comp(q, k, v, mask, stream)
+    torch.cuda.synchronize()
+    events = not args.no_phase_events
+    pkg.meda_profile_enable(events)
+    pkg.meda_profile_read(reset=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out = comp(q, k, v, mask, stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    phase_ms, n_calls = pkg.meda_profile_read(reset=True)
+    pkg.meda_profile_enable(False)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    budgets = out.layer_len.cpu().tolist()
+    work = algorithmic_work(wl, budgets)
+    names = [pkg.meda_phase_name(i) for i in range(pkg.N_PHASES)]
+    per_phase = {n: (phase_ms[i] / n_calls if n_calls else None) for i, n in enumerate(names)}
+
+    roofline = None
+    if n_calls:
+        dom = max(names, key=lambda n: per_phase[n])
+        bound = PHASE_BOUND[dom]
+        t_s = per_phase[dom] * 1e-3
+        if bound == "mfma":
+            achieved, peak, unit = work[dom] / t_s / 1e12, MFMA_PEAK_TFLOPS[wl.dtype], "TFLOP/s"
+        else:
+            achieved, peak, unit = work[dom] / t_s / 1e9, HBM_PEAK_GBS, "GB/s"
+        roofline = {"kernel": dom, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+                    "frac": achieved / peak, "traffic": None, "kernel_ms": per_phase[dom]}
+
+    e = 2 if wl.dtype == "bf16" else 4
+    alg_bytes = work["merge_write"]        # K and V once + the output: the traffic of the whole pass
+    rec = {
+        "metric": "kv_tokens_compressed_per_sec", "value": wl.seq_len / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
+        "data": "synthetic",
+        "config": {"workload": wl.name, "layers": wl.n_layers, "q_heads": wl.n_q_heads, "kv_heads": wl.n_kv_heads,
+                   "head_dim": wl.head_dim, "seq_len": wl.seq_len, "window": wl.window,
+                   "total_budget": wl.total_budget, "seed": wl.seed},
+        "kv_rows_per_sec": wl.n_layers * wl.n_kv_heads * wl.seq_len / (ms_per_step * 1e-3),
+        "pass_hbm_frac": (alg_bytes / (ms_per_step * 1e-3)) / (HBM_PEAK_GBS * 1e9),
+        "pass_mfma_frac": ((work["similarity"] + 2.0 * wl.n_layers * wl.n_q_heads * wl.window * wl.seq_len * wl.head_dim)
+                           / (ms_per_step * 1e-3)) / (MFMA_PEAK_TFLOPS[wl.dtype] * 1e12),
+        "phase_ms": per_phase,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()
