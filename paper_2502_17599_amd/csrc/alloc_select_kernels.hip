@@ -142,6 +142,8 @@ struct SelectArgs {
   const int32_t* alloc;
   const int64_t* off;
   int32_t* sel_idx;         // ragged [B*Hkv]
+  float* sel_inv_norm;      // ragged [B*Hkv]: 1/|k| of every conserved key
+  const float* inv_norm;    // [L][Hkv][T]
   int32_t* sel_idx_user;    // may be null
   int32_t* less_idx;        // ragged [(L*T-B)*Hkv]
   int32_t* merge_assign;    // may be null, [L][Hkv][T]
@@ -264,6 +266,7 @@ __global__ void __launch_bounds__(kSelThreads) select_kernel(SelectArgs a) {
     }
     if (sel) {
       a.sel_idx[c_base + pos_c] = j;
+      a.sel_inv_norm[c_base + pos_c] = a.inv_norm[(size_t)(l * a.Hkv + g) * T + j];
       if (a.sel_idx_user) a.sel_idx_user[c_base + pos_c] = j;
       if (a.merge_assign) a.merge_assign[(size_t)(l * a.Hkv + g) * T + j] = pos_c;
     } else if (valid) {
@@ -298,6 +301,8 @@ hipError_t launch_select(const Plan& p, const Buffers& b, hipStream_t s) {
   a.alloc = reinterpret_cast<const int32_t*>(b.ws + p.off_alloc);
   a.off = reinterpret_cast<const int64_t*>(b.ws + p.off_layer_off);
   a.sel_idx = reinterpret_cast<int32_t*>(b.ws + p.off_sel_idx);
+  a.sel_inv_norm = reinterpret_cast<float*>(b.ws + p.off_sel_inv);
+  a.inv_norm = reinterpret_cast<const float*>(b.ws + p.off_inv_norm);
   a.sel_idx_user = b.sel_idx_user;
   a.less_idx = reinterpret_cast<int32_t*>(b.ws + p.off_less_idx);
   a.merge_assign = b.merge_assign;

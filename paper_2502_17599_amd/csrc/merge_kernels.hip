@@ -16,6 +16,7 @@ struct MergeArgs {
   const int32_t* alloc;     // [L][4]
   const int64_t* off;       // [L+1]
   const int32_t* sel_idx;   // ragged conserved positions
+  const float* sel_inv_norm;  // ragged: 1/|k| of the conserved keys
   const int32_t* less_idx;  // ragged less-important positions (ascending)
   int32_t* less_slot;       // ragged: slot each of them merges into
   int32_t* sort_key[2];     // ping-pong buffers of the segment sort
@@ -39,15 +40,51 @@ __device__ __forceinline__ int sort_passes(int S) {
 // ------------------------------------------------------------------------ similarity + argmax
 // grid (ceil(T / 256), Hkv, L); 4 waves x 64 less-important rows.  Each wave keeps its rows as two
 // A-operand fragments in registers for the whole kernel and streams the conserved keys of its
-// (layer, head) through LDS in tiles of 64 slots.  u_ij = (k_i . k_j) / (|k_i| |k_j|): the raw keys
-// are multiplied (bf16 products are exact in the fp32 accumulator), the column factor 1/|k_j| is
-// applied to the accumulator, and the positive row factor 1/|k_i| is dropped because it cannot
-// change the argmax over j.  Ties go to the lower slot.
-template <typename T, int D>
-__global__ void __launch_bounds__(kSimWaves * 64) similarity_argmax_kernel(MergeArgs a) {
+// (layer, head) through LDS in tiles of 64 slots (double buffered: the global loads of tile t+1 and
+// the position loads of tile t+2 are in flight while tile t is multiplied).
+// u_ij = (k_i . k_j) / (|k_i| |k_j|): the raw keys are multiplied (bf16 products are exact in the
+// fp32 accumulator), the column factor 1/|k_j| is applied to the accumulator, and the positive row
+// factor 1/|k_i| is dropped because it cannot change the argmax over j.  Ties go to the lower slot.
+template <bool TAIL>
+__device__ __forceinline__ void argmax_update(const f32x16_t& acc, float iv, int slot, bool slot_ok,
+                                              float (&best)[16], int (&bidx)[16]) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const float u = acc[r] * iv;
+    const bool better = TAIL ? (slot_ok && u > best[r]) : (u > best[r]);
+    best[r] = better ? u : best[r];
+    bidx[r] = better ? slot : bidx[r];
+  }
+}
+
+template <typename T, int D, bool TAIL>
+__device__ __forceinline__ void sim_tile(const char* ctile, const float* cinv, int s0, int S, int n, int kg,
+                                         const Frag<T, D> (&af)[2], float (&best)[2][16], int (&bidx)[2][16]) {
   using TL = Tile<T, D>;
-  __shared__ __align__(16) char ctile[kSimSlotTile * TL::kStride];
-  __shared__ float cinv[kSimSlotTile];
+#pragma unroll
+  for (int cb = 0; cb < kSimSlotTile / 32; ++cb) {
+    if (TAIL && s0 + cb * 32 >= S) break;
+    Frag<T, D> bf;
+    frag_load(bf, ctile + (cb * 32 + n) * TL::kStride, kg);
+    const float iv = cinv[cb * 32 + n];
+    const int slot = s0 + cb * 32 + n;
+    f32x16_t acc0 = acc_zero(), acc1 = acc_zero();
+    mma<T, D>(acc0, af[0], bf);
+    mma<T, D>(acc1, af[1], bf);
+    argmax_update<TAIL>(acc0, iv, slot, slot < S, best[0], bidx[0]);
+    argmax_update<TAIL>(acc1, iv, slot, slot < S, best[1], bidx[1]);
+  }
+}
+
+template <typename T, int D>
+__global__ void __launch_bounds__(kSimWaves * 64, 2) similarity_argmax_kernel(MergeArgs a) {
+  using TL = Tile<T, D>;
+  constexpr int CPR = TL::kChunksPerRow;
+  constexpr int NTHR = kSimWaves * 64;
+  constexpr int PF = kSimSlotTile * CPR / NTHR;  // 16-byte pieces of a tile per thread
+  static_assert(kSimSlotTile * CPR % NTHR == 0, "tile pieces must divide evenly over the threads");
+  __shared__ __align__(16) char ctile[2][kSimSlotTile * TL::kStride];
+  __shared__ float cinv[2][kSimSlotTile];
 
   const int g = blockIdx.y, l = blockIdx.z;
   const int S = a.alloc[4 * l];
@@ -57,11 +94,12 @@ __global__ void __launch_bounds__(kSimWaves * 64) similarity_argmax_kernel(Merge
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, kg = lane >> 5;
   const long long off_l = a.off[l];
-  const int32_t* cidx = a.sel_idx + (size_t)off_l * a.Hkv + (size_t)g * S;
+  const size_t cbase = (size_t)off_l * a.Hkv + (size_t)g * S;
+  const int32_t* cidx = a.sel_idx + cbase;
+  const float* sinv = a.sel_inv_norm + cbase;
   const size_t lbase = less_base_of(l, g, a.T, a.Hkv, off_l, S);
   const int32_t* less = a.less_idx + lbase;
   const char* kbase = a.k + (size_t)(l * a.Hkv + g) * a.T * TL::kRowBytes;
-  const float* invn = a.inv_norm + (size_t)(l * a.Hkv + g) * a.T;
 
   Frag<T, D> af[2];
   const int r0 = row_base + wave * kSimRowsPerWave;
@@ -83,53 +121,55 @@ __global__ void __launch_bounds__(kSimWaves * 64) similarity_argmax_kernel(Merge
       bidx[s][r] = 0;
     }
 
-  constexpr int CPR = TL::kChunksPerRow;
-  for (int s0 = 0; s0 < S; s0 += kSimSlotTile) {
-    __syncthreads();
-    const int nslots = min(kSimSlotTile, S - s0);
-    for (int c = tid; c < kSimSlotTile * CPR; c += kSimWaves * 64) {
-      const int row = c / CPR, cc = c - row * CPR;
-      uint4 val = make_uint4(0, 0, 0, 0);
-      if (row < nslots)
-        val = *reinterpret_cast<const uint4*>(kbase + (size_t)cidx[s0 + row] * TL::kRowBytes + cc * 16);
-      *reinterpret_cast<uint4*>(ctile + row * TL::kStride + cc * 16) = val;
-    }
-    if (tid < kSimSlotTile) cinv[tid] = (tid < nslots) ? invn[cidx[s0 + tid]] : 0.f;
-    __syncthreads();
-    const bool tail = nslots < kSimSlotTile;
+  // this thread's pieces of a tile: piece i is 16 bytes at (row_i, cc_i)
+  int prow[PF], pcc[PF], pidx[PF];
 #pragma unroll
-    for (int cb = 0; cb < kSimSlotTile / 32; ++cb) {
-      if (s0 + cb * 32 < S) {
-        Frag<T, D> bf;
-        frag_load(bf, ctile + (cb * 32 + n) * TL::kStride, kg);
-        const float iv = cinv[cb * 32 + n];
-        const int slot = s0 + cb * 32 + n;
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-          f32x16_t acc = acc_zero();
-          mma<T, D>(acc, af[s], bf);
-          if (!tail) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const float u = acc[r] * iv;
-              const bool better = u > best[s][r];
-              best[s][r] = better ? u : best[s][r];
-              bidx[s][r] = better ? slot : bidx[s][r];
-            }
-          } else {
-            const bool slot_ok = slot < S;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const float u = acc[r] * iv;
-              const bool better = slot_ok && u > best[s][r];
-              best[s][r] = better ? u : best[s][r];
-              bidx[s][r] = better ? slot : bidx[s][r];
-            }
-          }
-        }
-      }
-    }
+  for (int i = 0; i < PF; ++i) {
+    const int c = tid + i * NTHR;
+    prow[i] = c / CPR;
+    pcc[i] = c - prow[i] * CPR;
   }
+  uint4 pre[PF];
+  float piv = 0.f;
+  const int ntiles = (S + kSimSlotTile - 1) / kSimSlotTile;
+  const int nfull = S / kSimSlotTile;
+
+#define MEDA_SIM_LOAD_IDX(t)                                          \
+  _Pragma("unroll") for (int i = 0; i < PF; ++i) {                    \
+    const int slot = (t) * kSimSlotTile + prow[i];                    \
+    pidx[i] = (slot < S) ? cidx[slot] : -1;                           \
+  }
+#define MEDA_SIM_ISSUE(t)                                                                                  \
+  _Pragma("unroll") for (int i = 0; i < PF; ++i) {                                                         \
+    pre[i] = make_uint4(0, 0, 0, 0);                                                                       \
+    if (pidx[i] >= 0)                                                                                      \
+      pre[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)pidx[i] * TL::kRowBytes + pcc[i] * 16);     \
+  }                                                                                                        \
+  if (tid < kSimSlotTile) piv = ((t) * kSimSlotTile + tid < S) ? sinv[(t) * kSimSlotTile + tid] : 0.f;
+#define MEDA_SIM_COMMIT(buf)                                                                               \
+  _Pragma("unroll") for (int i = 0; i < PF; ++i)                                                           \
+    *reinterpret_cast<uint4*>(ctile[buf] + prow[i] * TL::kStride + pcc[i] * 16) = pre[i];                  \
+  if (tid < kSimSlotTile) cinv[buf][tid] = piv;
+
+  MEDA_SIM_LOAD_IDX(0)
+  MEDA_SIM_ISSUE(0)
+  if (ntiles > 1) { MEDA_SIM_LOAD_IDX(1) }
+  MEDA_SIM_COMMIT(0)
+  for (int t = 0; t < ntiles; ++t) {
+    __syncthreads();  // tile t is in LDS; the other buffer is no longer read
+    if (t + 1 < ntiles) {
+      MEDA_SIM_ISSUE(t + 1)
+      if (t + 2 < ntiles) { MEDA_SIM_LOAD_IDX(t + 2) }
+    }
+    if (t < nfull)
+      sim_tile<T, D, false>(ctile[t & 1], cinv[t & 1], t * kSimSlotTile, S, n, kg, af, best, bidx);
+    else
+      sim_tile<T, D, true>(ctile[t & 1], cinv[t & 1], t * kSimSlotTile, S, n, kg, af, best, bidx);
+    if (t + 1 < ntiles) { MEDA_SIM_COMMIT((t + 1) & 1) }
+  }
+#undef MEDA_SIM_LOAD_IDX
+#undef MEDA_SIM_ISSUE
+#undef MEDA_SIM_COMMIT
 
   // argmax over the 32 lanes that hold different slots of the same row; ties -> lower slot
 #pragma unroll
@@ -382,6 +422,7 @@ static MergeArgs make_args(const Plan& p, const Buffers& b) {
   a.alloc = reinterpret_cast<const int32_t*>(b.ws + p.off_alloc);
   a.off = reinterpret_cast<const int64_t*>(b.ws + p.off_layer_off);
   a.sel_idx = reinterpret_cast<const int32_t*>(b.ws + p.off_sel_idx);
+  a.sel_inv_norm = reinterpret_cast<const float*>(b.ws + p.off_sel_inv);
   a.less_idx = reinterpret_cast<const int32_t*>(b.ws + p.off_less_idx);
   a.less_slot = reinterpret_cast<int32_t*>(b.ws + p.off_less_slot);
   a.sort_key[0] = reinterpret_cast<int32_t*>(b.ws + p.off_sort_a);
