@@ -38,53 +38,76 @@ __device__ __forceinline__ int sort_passes(int S) {
 }
 
 // ------------------------------------------------------------------------ similarity + argmax
-// grid (ceil(T / 256), Hkv, L); 4 waves x 64 less-important rows.  Each wave keeps its rows as two
-// A-operand fragments in registers for the whole kernel and streams the conserved keys of its
-// (layer, head) through LDS in tiles of 64 slots (double buffered: the global loads of tile t+1 and
-// the position loads of tile t+2 are in flight while tile t is multiplied).
-// u_ij = (k_i . k_j) / (|k_i| |k_j|): the raw keys are multiplied (bf16 products are exact in the
-// fp32 accumulator), the column factor 1/|k_j| is applied to the accumulator, and the positive row
-// factor 1/|k_i| is dropped because it cannot change the argmax over j.  Ties go to the lower slot.
+// grid (ceil(T / 256), Hkv, L); 4 waves x 64 less-important rows.  u_ij = (k_i . k_j)/(|k_i| |k_j|):
+// the raw keys are multiplied (bf16 products are exact in the fp32 accumulator), the factor 1/|k_j|
+// of the conserved key is applied to the accumulator, and the positive factor 1/|k_i| of the row is
+// dropped because it cannot change the argmax over j.  Ties go to the lower slot.
+//
+// Each wave keeps its 64 rows as two B-operand fragments in registers for the whole kernel and
+// streams the conserved keys of its (layer, head) through LDS as A operands, in tiles of 64 slots
+// (double buffered: the global loads of tile t+1 and the position loads of tile t+2 are in flight
+// while tile t is multiplied).  With the conserved keys as operand A, a lane owns ONE row and sees
+// 16 candidate slots per 32x32 block in its 16 accumulator registers: the running best of the row is
+// a single (value, slot) pair per lane, the block maximum is a max3 tree, and the search for the slot
+// that reached it only runs in blocks where some lane of the wave improved.
 template <bool TAIL>
-__device__ __forceinline__ void argmax_update(const f32x16_t& acc, float iv, int slot, bool slot_ok,
-                                              float (&best)[16], int (&bidx)[16]) {
+__device__ __forceinline__ void argmax_block(const f32x16_t& acc, const float (&iv)[16], int slot0, int kg, int S,
+                                             float& best, int& bidx) {
+  float u[16];
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    const float u = acc[r] * iv;
-    const bool better = TAIL ? (slot_ok && u > best[r]) : (u > best[r]);
-    best[r] = better ? u : best[r];
-    bidx[r] = better ? slot : bidx[r];
+    u[r] = acc[r] * iv[r];
+    if (TAIL) u[r] = (slot0 + acc_row(r, kg) < S) ? u[r] : -INFINITY;
+  }
+  float bm = fmaxf(u[0], u[1]);
+#pragma unroll
+  for (int r = 2; r < 16; r += 2) bm = fmaxf(bm, fmaxf(u[r], u[r + 1]));
+  const bool improved = bm > best;
+  if (__ballot(improved) != 0ull) {
+    int ridx = 15;
+#pragma unroll
+    for (int r = 14; r >= 0; --r) ridx = (u[r] != bm) ? ridx : r;  // lowest register that holds the maximum
+    best = improved ? bm : best;
+    bidx = improved ? slot0 + acc_row(ridx, kg) : bidx;
   }
 }
 
 template <typename T, int D, bool TAIL>
 __device__ __forceinline__ void sim_tile(const char* ctile, const float* cinv, int s0, int S, int n, int kg,
-                                         const Frag<T, D> (&af)[2], float (&best)[2][16], int (&bidx)[2][16]) {
+                                         const Frag<T, D> (&lf)[2], float (&best)[2], int (&bidx)[2]) {
   using TL = Tile<T, D>;
 #pragma unroll
   for (int cb = 0; cb < kSimSlotTile / 32; ++cb) {
     if (TAIL && s0 + cb * 32 >= S) break;
-    Frag<T, D> bf;
-    frag_load(bf, ctile + (cb * 32 + n) * TL::kStride, kg);
-    const float iv = cinv[cb * 32 + n];
-    const int slot = s0 + cb * 32 + n;
+    Frag<T, D> cf;
+    frag_load(cf, ctile + (cb * 32 + n) * TL::kStride, kg);
+    float iv[16];
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      const float4 v = *reinterpret_cast<const float4*>(cinv + cb * 32 + r4 * 8 + kg * 4);
+      iv[r4 * 4 + 0] = v.x;
+      iv[r4 * 4 + 1] = v.y;
+      iv[r4 * 4 + 2] = v.z;
+      iv[r4 * 4 + 3] = v.w;
+    }
     f32x16_t acc0 = acc_zero(), acc1 = acc_zero();
-    mma<T, D>(acc0, af[0], bf);
-    mma<T, D>(acc1, af[1], bf);
-    argmax_update<TAIL>(acc0, iv, slot, slot < S, best[0], bidx[0]);
-    argmax_update<TAIL>(acc1, iv, slot, slot < S, best[1], bidx[1]);
+    mma<T, D>(acc0, cf, lf[0]);
+    mma<T, D>(acc1, cf, lf[1]);
+    argmax_block<TAIL>(acc0, iv, s0 + cb * 32, kg, S, best[0], bidx[0]);
+    argmax_block<TAIL>(acc1, iv, s0 + cb * 32, kg, S, best[1], bidx[1]);
   }
 }
 
 template <typename T, int D>
-__global__ void __launch_bounds__(kSimWaves * 64, 2) similarity_argmax_kernel(MergeArgs a) {
+__global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 ? 2 : 1)) similarity_argmax_kernel(MergeArgs a) {
   using TL = Tile<T, D>;
   constexpr int CPR = TL::kChunksPerRow;
   constexpr int NTHR = kSimWaves * 64;
   constexpr int PF = kSimSlotTile * CPR / NTHR;  // 16-byte pieces of a tile per thread
-  static_assert(kSimSlotTile * CPR % NTHR == 0, "tile pieces must divide evenly over the threads");
+  constexpr int ROWS_PER_PIECE_STEP = NTHR / CPR;
+  static_assert(kSimSlotTile * CPR % NTHR == 0 && NTHR % CPR == 0, "tile pieces must divide evenly over the threads");
   __shared__ __align__(16) char ctile[2][kSimSlotTile * TL::kStride];
-  __shared__ float cinv[2][kSimSlotTile];
+  __shared__ __align__(16) float cinv[2][kSimSlotTile];
 
   const int g = blockIdx.y, l = blockIdx.z;
   const int S = a.alloc[4 * l];
@@ -101,54 +124,42 @@ __global__ void __launch_bounds__(kSimWaves * 64, 2) similarity_argmax_kernel(Me
   const int32_t* less = a.less_idx + lbase;
   const char* kbase = a.k + (size_t)(l * a.Hkv + g) * a.T * TL::kRowBytes;
 
-  Frag<T, D> af[2];
+  Frag<T, D> lf[2];
   const int r0 = row_base + wave * kSimRowsPerWave;
 #pragma unroll
   for (int s = 0; s < 2; ++s) {
     const int ri = r0 + s * 32 + n;
     if (ri < n_less)
-      frag_load(af[s], kbase + (size_t)less[ri] * TL::kRowBytes, kg);
+      frag_load(lf[s], kbase + (size_t)less[ri] * TL::kRowBytes, kg);
     else
-      frag_zero(af[s]);
+      frag_zero(lf[s]);
   }
-  float best[2][16];
-  int bidx[2][16];
-#pragma unroll
-  for (int s = 0; s < 2; ++s)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      best[s][r] = -INFINITY;
-      bidx[s][r] = 0;
-    }
+  float best[2] = {-INFINITY, -INFINITY};
+  int bidx[2] = {0, 0};
 
-  // this thread's pieces of a tile: piece i is 16 bytes at (row_i, cc_i)
-  int prow[PF], pcc[PF], pidx[PF];
-#pragma unroll
-  for (int i = 0; i < PF; ++i) {
-    const int c = tid + i * NTHR;
-    prow[i] = c / CPR;
-    pcc[i] = c - prow[i] * CPR;
-  }
+  // this thread's pieces of a tile: piece i is 16 bytes at row prow0 + i * ROWS_PER_PIECE_STEP, column pcc
+  const int prow0 = tid / CPR, pcc = tid - prow0 * CPR;
+  int pidx[PF];
   uint4 pre[PF];
   float piv = 0.f;
   const int ntiles = (S + kSimSlotTile - 1) / kSimSlotTile;
   const int nfull = S / kSimSlotTile;
 
-#define MEDA_SIM_LOAD_IDX(t)                                          \
-  _Pragma("unroll") for (int i = 0; i < PF; ++i) {                    \
-    const int slot = (t) * kSimSlotTile + prow[i];                    \
-    pidx[i] = (slot < S) ? cidx[slot] : -1;                           \
+#define MEDA_SIM_LOAD_IDX(t)                                                      \
+  _Pragma("unroll") for (int i = 0; i < PF; ++i) {                                \
+    const int slot = (t) * kSimSlotTile + prow0 + i * ROWS_PER_PIECE_STEP;        \
+    pidx[i] = (slot < S) ? cidx[slot] : -1;                                       \
   }
-#define MEDA_SIM_ISSUE(t)                                                                                  \
-  _Pragma("unroll") for (int i = 0; i < PF; ++i) {                                                         \
-    pre[i] = make_uint4(0, 0, 0, 0);                                                                       \
-    if (pidx[i] >= 0)                                                                                      \
-      pre[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)pidx[i] * TL::kRowBytes + pcc[i] * 16);     \
-  }                                                                                                        \
+#define MEDA_SIM_ISSUE(t)                                                                                \
+  _Pragma("unroll") for (int i = 0; i < PF; ++i) {                                                       \
+    pre[i] = make_uint4(0, 0, 0, 0);                                                                     \
+    if (pidx[i] >= 0)                                                                                    \
+      pre[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)pidx[i] * TL::kRowBytes + pcc * 16);      \
+  }                                                                                                      \
   if (tid < kSimSlotTile) piv = ((t) * kSimSlotTile + tid < S) ? sinv[(t) * kSimSlotTile + tid] : 0.f;
-#define MEDA_SIM_COMMIT(buf)                                                                               \
-  _Pragma("unroll") for (int i = 0; i < PF; ++i)                                                           \
-    *reinterpret_cast<uint4*>(ctile[buf] + prow[i] * TL::kStride + pcc[i] * 16) = pre[i];                  \
+#define MEDA_SIM_COMMIT(buf)                                                                             \
+  _Pragma("unroll") for (int i = 0; i < PF; ++i)                                                         \
+    *reinterpret_cast<uint4*>(ctile[buf] + (prow0 + i * ROWS_PER_PIECE_STEP) * TL::kStride + pcc * 16) = pre[i]; \
   if (tid < kSimSlotTile) cinv[buf][tid] = piv;
 
   MEDA_SIM_LOAD_IDX(0)
@@ -162,38 +173,28 @@ __global__ void __launch_bounds__(kSimWaves * 64, 2) similarity_argmax_kernel(Me
       if (t + 2 < ntiles) { MEDA_SIM_LOAD_IDX(t + 2) }
     }
     if (t < nfull)
-      sim_tile<T, D, false>(ctile[t & 1], cinv[t & 1], t * kSimSlotTile, S, n, kg, af, best, bidx);
+      sim_tile<T, D, false>(ctile[t & 1], cinv[t & 1], t * kSimSlotTile, S, n, kg, lf, best, bidx);
     else
-      sim_tile<T, D, true>(ctile[t & 1], cinv[t & 1], t * kSimSlotTile, S, n, kg, af, best, bidx);
+      sim_tile<T, D, true>(ctile[t & 1], cinv[t & 1], t * kSimSlotTile, S, n, kg, lf, best, bidx);
     if (t + 1 < ntiles) { MEDA_SIM_COMMIT((t + 1) & 1) }
   }
 #undef MEDA_SIM_LOAD_IDX
 #undef MEDA_SIM_ISSUE
 #undef MEDA_SIM_COMMIT
 
-  // argmax over the 32 lanes that hold different slots of the same row; ties -> lower slot
+  // the two lane groups saw disjoint slots of the same row: keep the better, ties -> lower slot
 #pragma unroll
-  for (int s = 0; s < 2; ++s)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      float bv = best[s][r];
-      int bi = bidx[s][r];
-#pragma unroll
-      for (int o = 1; o < 32; o <<= 1) {
-        const float ov = __shfl_xor(bv, o, kWave);
-        const int oi = __shfl_xor(bi, o, kWave);
-        const bool take = ov > bv || (ov == bv && oi < bi);
-        bv = take ? ov : bv;
-        bi = take ? oi : bi;
-      }
-      if (n == r) {
-        const int ri = r0 + s * 32 + acc_row(r, kg);
-        if (ri < n_less) {
-          a.less_slot[lbase + ri] = bi;
-          if (a.merge_assign) a.merge_assign[(size_t)(l * a.Hkv + g) * a.T + less[ri]] = bi;
-        }
-      }
+  for (int s = 0; s < 2; ++s) {
+    const float ov = __shfl_xor(best[s], 32, kWave);
+    const int oi = __shfl_xor(bidx[s], 32, kWave);
+    const bool take = ov > best[s] || (ov == best[s] && oi < bidx[s]);
+    const int bi = take ? oi : bidx[s];
+    const int ri = r0 + s * 32 + n;
+    if (kg == 0 && ri < n_less) {
+      a.less_slot[lbase + ri] = bi;
+      if (a.merge_assign) a.merge_assign[(size_t)(l * a.Hkv + g) * a.T + less[ri]] = bi;
     }
+  }
 }
 
 // ------------------------------------------------------------------------------- segment sort
