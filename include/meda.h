@@ -78,7 +78,8 @@ size_t meda_workspace_bytes(const meda_params* params);
  *   entropy        [L]   double E_CM per layer; may be NULL
  *   sel_idx        [B*Hkv] int32 original position of every output row, same ragged layout; may be NULL
  *   merge_assign   [L][Hkv][T] int32 for every position the slot (row within its (layer, head)
- *                  block) it was kept in or merged into; may be NULL
+ *                  block) it was kept in or merged into (-1 for evicted positions when
+ *                  MEDA_FLAG_NO_MERGE is set); may be NULL
  *   workspace      at least meda_workspace_bytes(params) bytes, 256-byte aligned
  *   hip_stream     hipStream_t (NULL = the default stream)
  * Calls that share a workspace must not overlap.
@@ -98,8 +99,8 @@ typedef enum {
   MEDA_REGION_ROW_STATS = 2,  /* float [L][Hq][Wp][4], Wp = W rounded up to 32: log2-domain row max,
                                  1/Z over all visible keys, 1/Z over the row's cross-modal keys, 0   */
   MEDA_REGION_ALLOC = 3,      /* int32 [L][4]: S_l, M_l, N_l, 0                                     */
-  MEDA_REGION_LESS_IDX = 4,   /* int32 ragged: layer l, head g at ((l*T - off[l])*Hkv + g*(T-S_l)):
-                                 positions that are not conserved, ascending                         */
+  MEDA_REGION_LESS_IDX = 4,   /* int32 ragged: layer l, head g at ((l*T - off[l])*Hkv + g*(T-S_l)): the keys
+                                 that are not conserved, ascending, as row ids (l*Hkv+g)*T + position */
   MEDA_REGION_LESS_SLOT = 5   /* int32, same layout: slot each of them merges into                   */
 } meda_region;
 meda_status meda_workspace_region(const meda_params* params, int region, size_t* offset, size_t* bytes);

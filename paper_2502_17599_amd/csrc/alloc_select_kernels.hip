@@ -141,17 +141,17 @@ struct SelectArgs {
   const uint8_t* mask;
   const int32_t* alloc;
   const int64_t* off;
-  int32_t* sel_idx;         // ragged [B*Hkv]
+  int32_t* sel_idx;         // ragged [B*Hkv]: row ids (l*Hkv+g)*T + position
   float* sel_inv_norm;      // ragged [B*Hkv]: 1/|k| of every conserved key
   const float* inv_norm;    // [L][Hkv][T]
   int32_t* sel_idx_user;    // may be null
-  int32_t* less_idx;        // ragged [(L*T-B)*Hkv]
+  int32_t* less_idx;        // ragged [(L*T-B)*Hkv]: row ids
   int32_t* merge_assign;    // may be null, [L][Hkv][T]
-  int L, Hkv, T;
+  int L, Hkv, T, no_merge;
 };
 
-constexpr int kSelThreads = 1024;
-constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kSelMaxThreads = 1024;
+constexpr int kSelMaxWaves = kSelMaxThreads / 64;
 
 // Exclusive rank of a one-bit flag over the workgroup (ballots inside a wave, wave totals in LDS).
 // `totals` has 2*kSelWaves ints; `slot` selects which half.  Returns rank; *block_total = number of set flags.
@@ -168,19 +168,21 @@ __device__ __forceinline__ int flag_rank_in_wave(bool flag, int lane, int* wave_
 // fp32 scores (no bits are lost to the addition) with a 4 x 8-bit radix select on their bit
 // patterns (scores are >= 0, so the unsigned order of the bits is the order of the values); equal
 // scores go to the smaller position.
-__global__ void __launch_bounds__(kSelThreads) select_kernel(SelectArgs a) {
+__global__ void __launch_bounds__(kSelMaxThreads) select_kernel(SelectArgs a) {
   __shared__ int hist[256];
-  __shared__ int wtot[2][kSelWaves];
-  __shared__ int s_red[kSelWaves];
+  __shared__ int wtot[2][kSelMaxWaves];
+  __shared__ int s_red[kSelMaxWaves];
   __shared__ unsigned s_prefix;
   __shared__ int s_remaining;
 
   const int g = blockIdx.x, l = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kSelThreads = blockDim.x, kSelWaves = kSelThreads >> 6;
   const int T = a.T;
   const int S = a.alloc[4 * l + 0], M = a.alloc[4 * l + 1], N = a.alloc[4 * l + 2];
   const int ncand = T - M;
   const long long off_l = a.off[l];
-  const float* scores = a.col_scores + (size_t)(l * a.Hkv + g) * T;
+  const int head_row0 = (l * a.Hkv + g) * T;  // row id of position 0 of this (layer, head)
+  const float* scores = a.col_scores + (size_t)head_row0;
   const size_t c_base = (size_t)off_l * a.Hkv + (size_t)g * S;
   const size_t less_base = ((size_t)l * T - (size_t)off_l) * a.Hkv + (size_t)g * (T - S);
 
@@ -214,14 +216,32 @@ __global__ void __launch_bounds__(kSelThreads) select_kernel(SelectArgs a) {
         }
       }
       __syncthreads();
-      if (tid == 0) {
-        int remaining = s_remaining, cum = 0, digit = 0;
-        for (int b = 255; b >= 0; --b) {
-          if (cum + hist[b] >= remaining) { digit = b; break; }
-          cum += hist[b];
+      if (wave == 0) {
+        // bins from the top: lane i looks at bins 255-4i .. 252-4i; the lane whose running count
+        // first reaches `remaining` holds the digit of the K-th largest key
+        const int remaining = s_remaining;
+        const int b0 = 255 - 4 * lane;
+        const int c0 = hist[b0], c1 = hist[b0 - 1], c2 = hist[b0 - 2], c3 = hist[b0 - 3];
+        const int tot = c0 + c1 + c2 + c3;
+        int inc = tot;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const int t = __shfl_up(inc, o, kWave);
+          if (lane >= o) inc += t;
         }
-        s_remaining = remaining - cum;
-        s_prefix = prefix | ((unsigned)digit << shift);
+        const int exc = inc - tot;
+        if (exc < remaining && inc >= remaining) {
+          int cum = exc, digit = b0;
+          if (cum + c0 < remaining) {
+            cum += c0; digit = b0 - 1;
+            if (cum + c1 < remaining) {
+              cum += c1; digit = b0 - 2;
+              if (cum + c2 < remaining) { cum += c2; digit = b0 - 3; }
+            }
+          }
+          s_remaining = remaining - cum;
+          s_prefix = prefix | ((unsigned)digit << shift);
+        }
       }
       prefix_mask |= 255u << shift;
       __syncthreads();
@@ -265,12 +285,13 @@ __global__ void __launch_bounds__(kSelThreads) select_kernel(SelectArgs a) {
       sel_total += v;
     }
     if (sel) {
-      a.sel_idx[c_base + pos_c] = j;
-      a.sel_inv_norm[c_base + pos_c] = a.inv_norm[(size_t)(l * a.Hkv + g) * T + j];
+      a.sel_idx[c_base + pos_c] = head_row0 + j;
+      a.sel_inv_norm[c_base + pos_c] = a.inv_norm[head_row0 + j];
       if (a.sel_idx_user) a.sel_idx_user[c_base + pos_c] = j;
-      if (a.merge_assign) a.merge_assign[(size_t)(l * a.Hkv + g) * T + j] = pos_c;
+      if (a.merge_assign) a.merge_assign[head_row0 + j] = pos_c;
     } else if (valid) {
-      a.less_idx[less_base + (j - pos_c)] = j;
+      a.less_idx[less_base + (j - pos_c)] = head_row0 + j;
+      if (a.merge_assign && a.no_merge) a.merge_assign[head_row0 + j] = -1;
     }
     run_c += sel_total;
     run_tie += tie_total;
@@ -306,8 +327,9 @@ hipError_t launch_select(const Plan& p, const Buffers& b, hipStream_t s) {
   a.sel_idx_user = b.sel_idx_user;
   a.less_idx = reinterpret_cast<int32_t*>(b.ws + p.off_less_idx);
   a.merge_assign = b.merge_assign;
-  a.L = p.L; a.Hkv = p.Hkv; a.T = p.T;
-  hipLaunchKernelGGL(select_kernel, dim3(p.Hkv, p.L), dim3(kSelThreads), 0, s, a);
+  a.L = p.L; a.Hkv = p.Hkv; a.T = p.T; a.no_merge = (p.flags & MEDA_FLAG_NO_MERGE) ? 1 : 0;
+  const int nthr = p.T >= 16384 ? 1024 : (p.T >= 4096 ? 512 : 256);
+  hipLaunchKernelGGL(select_kernel, dim3(p.Hkv, p.L), dim3(nthr), 0, s, a);
   return hipGetLastError();
 }
 

@@ -73,7 +73,8 @@ meda_status make_plan(const meda_params* p, Plan* out) {
   pl.off_sort_b = take(less_bytes);
   pl.off_sort_c = take(less_bytes);
   pl.off_sort_d = take(less_bytes);
-  pl.off_seg_start = take(((size_t)pl.B * pl.Hkv + (size_t)pl.L * pl.Hkv) * 4 + 16);
+  pl.off_seg_beg = take((size_t)pl.B * pl.Hkv * 4);
+  pl.off_seg_end = take((size_t)pl.B * pl.Hkv * 4);
   pl.total_bytes = o;
   *out = pl;
   return MEDA_OK;

@@ -15,15 +15,17 @@ struct MergeArgs {
   const float* inv_norm;    // [L][Hkv][T]
   const int32_t* alloc;     // [L][4]
   const int64_t* off;       // [L+1]
-  const int32_t* sel_idx;   // ragged conserved positions
+  const int32_t* sel_idx;   // ragged [B*Hkv]: row id (l*Hkv+g)*T + position of every conserved key
   const float* sel_inv_norm;  // ragged: 1/|k| of the conserved keys
-  const int32_t* less_idx;  // ragged less-important positions (ascending)
+  const int32_t* less_idx;  // ragged: row ids of the less-important keys (ascending)
   int32_t* less_slot;       // ragged: slot each of them merges into
   int32_t* sort_key[2];     // ping-pong buffers of the segment sort
   int32_t* sort_val[2];
-  int32_t* seg_start;       // ragged [B*Hkv + L*Hkv]: (S_l + 1) entries per (layer, head)
+  int32_t* seg_beg;         // [B*Hkv]: members of output row w are sort_val[0][seg_beg[w] .. seg_end[w])
+  int32_t* seg_end;
   int32_t* merge_assign;    // may be null
   int L, Hkv, T, flags;
+  int merge_members;        // 0: every output row is a plain copy (no merge requested or nothing to merge)
   long long total_slots;    // B * Hkv
 };
 
@@ -122,7 +124,7 @@ __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 
   const float* sinv = a.sel_inv_norm + cbase;
   const size_t lbase = less_base_of(l, g, a.T, a.Hkv, off_l, S);
   const int32_t* less = a.less_idx + lbase;
-  const char* kbase = a.k + (size_t)(l * a.Hkv + g) * a.T * TL::kRowBytes;
+  const char* kbase = a.k;  // positions are stored as row ids over all layers and heads
 
   Frag<T, D> lf[2];
   const int r0 = row_base + wave * kSimRowsPerWave;
@@ -192,16 +194,16 @@ __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 
     const int ri = r0 + s * 32 + n;
     if (kg == 0 && ri < n_less) {
       a.less_slot[lbase + ri] = bi;
-      if (a.merge_assign) a.merge_assign[(size_t)(l * a.Hkv + g) * a.T + less[ri]] = bi;
+      if (a.merge_assign) a.merge_assign[less[ri]] = bi;
     }
   }
 }
 
 // ------------------------------------------------------------------------------- segment sort
 // grid (Hkv, L); 1024 threads.  Stable least-significant-digit radix sort (4 bits per pass) of the
-// pairs (slot, position) of one (layer, head) by slot; positions enter ascending, so every slot's
-// members come out ascending and the merge adds them in one fixed order.  Then seg_start[s] = first
-// sorted index whose slot is >= s.
+// pairs (slot, row id) of one (layer, head) by slot; row ids enter ascending, so every slot's
+// members come out ascending and the merge adds them in one fixed order.  The last pass always
+// writes buffer 0.  Then seg_beg / seg_end of every slot = its range in the sorted array.
 constexpr int kSortThreads = 1024;
 constexpr int kSortWaves = kSortThreads / 64;
 
@@ -220,8 +222,9 @@ __global__ void __launch_bounds__(kSortThreads) segment_sort_kernel(MergeArgs a)
   const int32_t* in_key = a.less_slot + lbase;
   const int32_t* in_val = a.less_idx + lbase;
   for (int p = 0; p < passes; ++p) {
-    int32_t* out_key = a.sort_key[p & 1] + lbase;
-    int32_t* out_val = a.sort_val[p & 1] + lbase;
+    const int ob = (passes - 1 - p) & 1;
+    int32_t* out_key = a.sort_key[ob] + lbase;
+    int32_t* out_val = a.sort_val[ob] + lbase;
     const int shift = 4 * p;
     if (tid < 16) base[tid] = 0;
     __syncthreads();
@@ -261,7 +264,7 @@ __global__ void __launch_bounds__(kSortThreads) segment_sort_kernel(MergeArgs a)
       for (int q = 0; q < 16; ++q) {
         const unsigned long long b = __ballot(dgt == q);
         if (dgt == q) my_rank = __popcll(b & lt_mask);
-        if (lane == 0) wcnt[wave][q] = __popcll(b);
+        if (lane == q) wcnt[wave][q] = __popcll(b);
       }
       __syncthreads();
       if (valid) {
@@ -282,15 +285,20 @@ __global__ void __launch_bounds__(kSortThreads) segment_sort_kernel(MergeArgs a)
     in_val = out_val;
   }
 
-  // segment starts from the sorted slots
-  int32_t* seg = a.seg_start + (size_t)off_l * a.Hkv + (size_t)g * S + (size_t)(l * a.Hkv + g);
+  // member range of every slot, as absolute indices into the sorted array
+  const size_t cbase = (size_t)off_l * a.Hkv + (size_t)g * S;
+  int32_t* beg = a.seg_beg + cbase;
+  int32_t* end = a.seg_end + cbase;
+  const int ib = (int)lbase;
   for (int i = tid; i < n; i += kSortThreads) {
     const int kcur = in_key[i];
     const int kprev = (i > 0) ? in_key[i - 1] : -1;
-    for (int s = kprev + 1; s <= kcur; ++s) seg[s] = i;
+    for (int s = kprev + 1; s <= kcur; ++s) beg[s] = ib + i;
+    for (int s = max(kprev, 0); s < kcur; ++s) end[s] = ib + i;
   }
   const int klast = (n > 0) ? in_key[n - 1] : -1;
-  for (int s = klast + 1 + tid; s <= S; s += kSortThreads) seg[s] = n;
+  for (int s = klast + 1 + tid; s < S; s += kSortThreads) beg[s] = ib + n;
+  for (int s = max(klast, 0) + tid; s < S; s += kSortThreads) end[s] = ib + n;
 }
 
 // ------------------------------------------------------------------------------ merge + write
@@ -312,11 +320,17 @@ struct OutConv<bf16_t> {
       out[2 * i + 1] = (double)__uint_as_float(w[i] & 0xffff0000u);
     }
   }
-  static __device__ __forceinline__ uint4 pack(const double* in) {
-    uint32_t w[4];
+  // store N consecutive elements sum[i] / denom, rounded once to bf16
+  template <int N>
+  static __device__ __forceinline__ void store(char* dst, const double* sum, double denom) {
+    if constexpr (N == 1) {
+      *reinterpret_cast<uint16_t*>(dst) = (uint16_t)double_to_bf16_bits(sum[0] / denom);
+    } else {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) w[i] = double_to_bf16_bits(in[2 * i]) | (double_to_bf16_bits(in[2 * i + 1]) << 16);
-    return make_uint4(w[0], w[1], w[2], w[3]);
+      for (int i = 0; i < N / 2; ++i)
+        reinterpret_cast<uint32_t*>(dst)[i] =
+            double_to_bf16_bits(sum[2 * i] / denom) | (double_to_bf16_bits(sum[2 * i + 1] / denom) << 16);
+    }
   }
 };
 template <>
@@ -328,9 +342,10 @@ struct OutConv<float> {
     out[2] = (double)__uint_as_float(v.z);
     out[3] = (double)__uint_as_float(v.w);
   }
-  static __device__ __forceinline__ uint4 pack(const double* in) {
-    return make_uint4(__float_as_uint(__double2float_rn(in[0])), __float_as_uint(__double2float_rn(in[1])),
-                      __float_as_uint(__double2float_rn(in[2])), __float_as_uint(__double2float_rn(in[3])));
+  template <int N>
+  static __device__ __forceinline__ void store(char* dst, const double* sum, double denom) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) reinterpret_cast<float*>(dst)[i] = __double2float_rn(sum[i] / denom);
   }
 };
 
@@ -345,32 +360,27 @@ __global__ void __launch_bounds__(256) merge_write_kernel(MergeArgs a) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const long long w = (long long)blockIdx.x * 4 + wave;
   if (w >= a.total_slots) return;
-  // layer of this output row: largest l with off[l]*Hkv <= w
-  int lo_l = 0, hi_l = a.L;
-  while (hi_l - lo_l > 1) {
-    const int mid = (lo_l + hi_l) >> 1;
-    if (a.off[mid] * a.Hkv <= w) lo_l = mid; else hi_l = mid;
+  // everything the wave needs is indexed by its output row w: no layer / head lookup
+  const int row0 = a.sel_idx[w];
+  int m_beg = 0, m_end = 0;
+  if (a.merge_members) {
+    m_beg = a.seg_beg[w];
+    m_end = a.seg_end[w];
   }
-  const int l = lo_l;
-  const long long off_l = a.off[l];
-  const int S = a.alloc[4 * l];
-  const long long rem = w - off_l * a.Hkv;
-  const int g = (int)(rem / S), s = (int)(rem - (long long)g * S);
-  const int pos = a.sel_idx[w];
-  int m_lo = 0, m_hi = 0;
-  const int32_t* members = nullptr;
-  if (!(a.flags & MEDA_FLAG_NO_MERGE) && a.T > S) {
-    const int32_t* seg = a.seg_start + w + (l * a.Hkv + g);
-    m_lo = seg[0];
-    m_hi = seg[1];
-    const int fin = (sort_passes(S) - 1) & 1;
-    members = a.sort_val[fin] + less_base_of(l, g, a.T, a.Hkv, off_l, S);
-  }
-  const int n_rows = m_hi - m_lo + 1;  // the conserved row and its members
+  const int32_t* members = a.sort_val[0];
+  const int n_rows = m_end - m_beg + 1;  // the conserved row and its members
   const int sub = lane / LPR, cc = lane - sub * LPR;
-  const size_t head_base = (size_t)(l * a.Hkv + g) * a.T * TL::kRowBytes;
-  const char* kb = a.k + head_base + cc * 16;
-  const char* vb = a.v + head_base + cc * 16;
+  const char* kb = a.k + cc * 16;
+  const char* vb = a.v + cc * 16;
+  if (n_rows == 1) {  // nothing merges into this row: bit-exact copy
+    if (sub == 0) {
+      *reinterpret_cast<uint4*>(a.k_out + (size_t)w * TL::kRowBytes + cc * 16) =
+          *reinterpret_cast<const uint4*>(kb + (size_t)row0 * TL::kRowBytes);
+      *reinterpret_cast<uint4*>(a.v_out + (size_t)w * TL::kRowBytes + cc * 16) =
+          *reinterpret_cast<const uint4*>(vb + (size_t)row0 * TL::kRowBytes);
+    }
+    return;
+  }
 
   double ak[E], av[E];
 #pragma unroll
@@ -378,37 +388,71 @@ __global__ void __launch_bounds__(256) merge_write_kernel(MergeArgs a) {
     ak[i] = 0.0;
     av[i] = 0.0;
   }
-  for (int e = sub; e < n_rows; e += MS) {
-    const int row = (e == 0) ? pos : members[m_lo + e - 1];
-    const uint4 kv = *reinterpret_cast<const uint4*>(kb + (size_t)row * TL::kRowBytes);
-    const uint4 vv = *reinterpret_cast<const uint4*>(vb + (size_t)row * TL::kRowBytes);
-    double tk[E], tv[E];
-    CV::unpack(kv, tk);
-    CV::unpack(vv, tv);
+  // element -1 of the list is the conserved row itself; 64 list entries are fetched per round with
+  // one coalesced load and handed to the lane groups by shuffles, so all row loads of a round can
+  // be in flight together
+  for (int base = m_beg - 1; base < m_end; base += 64) {
+    const int mine_i = base + lane;
+    const int mine = (mine_i < m_beg) ? row0 : ((mine_i < m_end) ? members[mine_i] : -1);
+    const int cnt = min(64, m_end - base);
+    for (int t = 0; t < cnt; t += 2 * MS) {
+      const int e0 = t + sub, e1 = t + MS + sub;
+      const int r0 = __shfl(mine, e0 & 63, kWave), r1 = __shfl(mine, e1 & 63, kWave);
+      const bool ok0 = e0 < cnt, ok1 = e1 < cnt;
+      uint4 k0 = make_uint4(0, 0, 0, 0), v0 = k0, k1 = k0, v1 = k0;
+      if (ok0) {
+        k0 = *reinterpret_cast<const uint4*>(kb + (size_t)r0 * TL::kRowBytes);
+        v0 = *reinterpret_cast<const uint4*>(vb + (size_t)r0 * TL::kRowBytes);
+      }
+      if (ok1) {
+        k1 = *reinterpret_cast<const uint4*>(kb + (size_t)r1 * TL::kRowBytes);
+        v1 = *reinterpret_cast<const uint4*>(vb + (size_t)r1 * TL::kRowBytes);
+      }
+      double tk[E], tv[E];
+      CV::unpack(k0, tk);
+      CV::unpack(v0, tv);
 #pragma unroll
-    for (int i = 0; i < E; ++i) {
-      ak[i] += tk[i];
-      av[i] += tv[i];
+      for (int i = 0; i < E; ++i) {
+        ak[i] += tk[i];
+        av[i] += tv[i];
+      }
+      CV::unpack(k1, tk);
+      CV::unpack(v1, tv);
+#pragma unroll
+      for (int i = 0; i < E; ++i) {
+        ak[i] += tk[i];
+        av[i] += tv[i];
+      }
     }
   }
+  // Reduce over the lane groups that read different rows.  Each exchange halves the elements a lane
+  // is responsible for (the lower group keeps the lower half), so after log2(MS) steps a lane holds
+  // E / MS finished sums starting at element `ebase` of its 16-byte piece: the divisions and the
+  // stores are spread over all 64 lanes.
+  int ebase = 0;
+  {
+    int len = E;
 #pragma unroll
-  for (int o = LPR; o < 64; o <<= 1) {
+    for (int step = 0; (LPR << step) < 64; ++step) {
+      len >>= 1;
+      const bool hi = (sub >> step) & 1;
 #pragma unroll
-    for (int i = 0; i < E; ++i) {
-      ak[i] += __shfl_xor(ak[i], o, kWave);
-      av[i] += __shfl_xor(av[i], o, kWave);
+      for (int i = 0; i < len; ++i) {
+        const double ks = hi ? ak[i] : ak[i + len], kk = hi ? ak[i + len] : ak[i];
+        const double vs = hi ? av[i] : av[i + len], vk = hi ? av[i + len] : av[i];
+        ak[i] = kk + __shfl_xor(ks, LPR << step, kWave);
+        av[i] = vk + __shfl_xor(vs, LPR << step, kWave);
+      }
+      ebase += hi ? len : 0;
     }
   }
-  if (sub == 0) {
-    const double denom = (double)n_rows;
-#pragma unroll
-    for (int i = 0; i < E; ++i) {
-      ak[i] /= denom;
-      av[i] /= denom;
-    }
-    *reinterpret_cast<uint4*>(a.k_out + (size_t)w * TL::kRowBytes + cc * 16) = CV::pack(ak);
-    *reinterpret_cast<uint4*>(a.v_out + (size_t)w * TL::kRowBytes + cc * 16) = CV::pack(av);
-  }
+  constexpr int EPL = E / MS;  // finished elements per lane
+  static_assert(EPL >= 1, "a lane must end up with at least one element");
+  const double denom = (double)n_rows;
+  char* ko = a.k_out + (size_t)w * TL::kRowBytes + cc * 16 + ebase * (int)sizeof(T);
+  char* vo = a.v_out + (size_t)w * TL::kRowBytes + cc * 16 + ebase * (int)sizeof(T);
+  CV::template store<EPL>(ko, ak, denom);
+  CV::template store<EPL>(vo, av, denom);
 }
 
 // ------------------------------------------------------------------------------------------ launch
@@ -430,10 +474,12 @@ static MergeArgs make_args(const Plan& p, const Buffers& b) {
   a.sort_val[0] = reinterpret_cast<int32_t*>(b.ws + p.off_sort_b);
   a.sort_key[1] = reinterpret_cast<int32_t*>(b.ws + p.off_sort_c);
   a.sort_val[1] = reinterpret_cast<int32_t*>(b.ws + p.off_sort_d);
-  a.seg_start = reinterpret_cast<int32_t*>(b.ws + p.off_seg_start);
+  a.seg_beg = reinterpret_cast<int32_t*>(b.ws + p.off_seg_beg);
+  a.seg_end = reinterpret_cast<int32_t*>(b.ws + p.off_seg_end);
   a.merge_assign = b.merge_assign;
   a.L = p.L; a.Hkv = p.Hkv; a.T = p.T; a.flags = p.flags;
   a.total_slots = (long long)p.B * p.Hkv;
+  a.merge_members = !((p.flags & MEDA_FLAG_NO_MERGE) || p.B == (int64_t)p.L * p.T);
   return a;
 }
 
