@@ -83,7 +83,20 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-phase-events", action="store_true",
                     help="do not record per-kernel HIP events inside the timed region")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
+                    help="only run a plain device copy of BYTES bytes five times (reference for the "
+                         "HBM byte counters of rocprofv3) and exit")
     args = ap.parse_args()
+    if args.copy_calibration:
+        import torch
+        src = torch.empty(args.copy_calibration, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": args.copy_calibration, "copies": 5}))
+        return
     if args.gpus != 1:
         print("bench.py: this build is single-GPU only (one MI355X holds all layers and heads); "
               "run with --gpus 1", file=sys.stderr)

@@ -119,6 +119,37 @@ __device__ __forceinline__ void tile_load_contiguous(char* lds, const char* gsrc
   }
 }
 
+// A tile of ROWS consecutive rows, cut in 16-byte pieces that are dealt round-robin to the threads of
+// the workgroup and held in registers between the global loads (all issued back to back, so they are
+// in flight together) and the stores into the padded LDS tile.  PIECES is sized for 256 threads;
+// larger workgroups leave the upper pieces unused.
+template <typename T, int D, int ROWS>
+struct TileStage {
+  static constexpr int CPR = Tile<T, D>::kChunksPerRow;
+  static constexpr int TOTAL = ROWS * CPR;
+  static constexpr int PIECES = (TOTAL + 255) / 256;
+  uint4 r[PIECES];
+
+  __device__ __forceinline__ void fetch(const char* gsrc, int rows_valid, int tid, int n_threads) {
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) {
+      const int c = tid + i * n_threads;
+      const int row = c / CPR, cc = c - row * CPR;
+      r[i] = make_uint4(0, 0, 0, 0);
+      if (c < TOTAL && row < rows_valid)
+        r[i] = *reinterpret_cast<const uint4*>(gsrc + (size_t)row * Tile<T, D>::kRowBytes + cc * 16);
+    }
+  }
+  __device__ __forceinline__ void commit(char* lds, int tid, int n_threads) const {
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) {
+      const int c = tid + i * n_threads;
+      const int row = c / CPR, cc = c - row * CPR;
+      if (c < TOTAL) *reinterpret_cast<uint4*>(lds + row * Tile<T, D>::kStride + cc * 16) = r[i];
+    }
+  }
+};
+
 // ---- element conversion -----------------------------------------------------------------------
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) { return __uint_as_float(bits16 << 16); }

@@ -47,6 +47,7 @@ __global__ void __launch_bounds__(512) score_stats_kernel(ScoreArgs a) {
   const int tid = threadIdx.x, nthr = blockDim.x;
   const int wave = tid >> 6, lane = tid & 63, n = lane & 31, kg = lane >> 5;
   const int cgi = wave % a.NCG, cs = wave / a.NCG;
+  const bool active = cs < a.CS;  // the workgroup is padded to 4 or 8 waves; spare waves only move data
   const int n_combos = a.G * a.RB;
 
   Frag<T, D> qf[NQ];
@@ -62,7 +63,7 @@ __global__ void __launch_bounds__(512) score_stats_kernel(ScoreArgs a) {
     qrow[q] = 0;
     qhead[q] = 0;
     frag_zero(qf[q]);
-    if (cidx < n_combos) {
+    if (active && cidx < n_combos) {
       nvalid = q + 1;
       const int hg = cidx / a.RB, rb = cidx - hg * a.RB;
       qhead[q] = g * a.G + hg;
@@ -77,12 +78,23 @@ __global__ void __launch_bounds__(512) score_stats_kernel(ScoreArgs a) {
   const char* kbase = a.k + (size_t)(l * a.Hkv + g) * a.T * TL::kRowBytes;
   float* invn_out = a.inv_norm + (size_t)(l * a.Hkv + g) * a.T;
 
+  TileStage<T, D, kScoreTile> stage;
+  uint8_t mreg = 0;
+  if (jbeg < jend) {
+    stage.fetch(kbase + (size_t)jbeg * TL::kRowBytes, min(kScoreTile, a.T - jbeg), tid, nthr);
+    if (tid < kScoreTile) mreg = (jbeg + tid < a.T) ? a.mask[jbeg + tid] : 0;
+  }
   for (int j0 = jbeg; j0 < jend; j0 += kScoreTile) {
-    __syncthreads();
+    __syncthreads();  // the previous tile is no longer read
     const int rows_valid = min(kScoreTile, a.T - j0);
-    tile_load_contiguous<T, D>(ktile, kbase + (size_t)j0 * TL::kRowBytes, kScoreTile, rows_valid, tid, nthr);
-    if (tid < kScoreTile) lmask[tid] = (j0 + tid < a.T) ? a.mask[j0 + tid] : 0;
+    stage.commit(ktile, tid, nthr);
+    if (tid < kScoreTile) lmask[tid] = mreg;
     __syncthreads();
+    if (j0 + kScoreTile < jend) {  // next tile's loads are in flight while this one is processed
+      const int jn = j0 + kScoreTile;
+      stage.fetch(kbase + (size_t)jn * TL::kRowBytes, min(kScoreTile, a.T - jn), tid, nthr);
+      if (tid < kScoreTile) mreg = (jn + tid < a.T) ? a.mask[jn + tid] : 0;
+    }
 
     // 1/|k| of the tile's keys: two threads per row
     for (int row = tid >> 1; row < kScoreTile; row += nthr >> 1) {
@@ -94,7 +106,7 @@ __global__ void __launch_bounds__(512) score_stats_kernel(ScoreArgs a) {
       if ((tid & 1) == 0 && row < rows_valid) invn_out[j0 + row] = 1.0f / fmaxf(sqrtf(ss), 1e-30f);
     }
 
-    for (int sb = cs; sb < kScoreTile / 32; sb += a.CS) {
+    for (int sb = cs; active && sb < kScoreTile / 32; sb += a.CS) {
       const int jb = j0 + sb * 32;
       if (jb >= a.T) break;
       Frag<T, D> kf;
@@ -226,55 +238,72 @@ __global__ void __launch_bounds__(256) score_accum_kernel(ScoreArgs a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) pbar[rb][r] = 0.f;
 
-  for (int g = 0; g < a.Hkv; ++g) {
-    Frag<T, D> kf;
-    float colsum = 0.f;
-    for (int hg = 0; hg < a.G; ++hg) {
-      const int h = g * a.G + hg;
-      __syncthreads();  // the previous head's tiles are no longer read
-      if (hg == 0)
-        tile_load_contiguous<T, D>(ktile, a.k + ((size_t)(l * a.Hkv + g) * a.T + j0) * TL::kRowBytes, kScoreTile,
-                                   rows_valid, tid, 256);
-      tile_load_contiguous<T, D>(qtile, a.q + (size_t)(l * a.Hq + h) * a.W * TL::kRowBytes, Wp, a.W, tid, 256);
-      if (tid < Wp) {
-        const float4 s = a.stats[(size_t)(l * a.Hq + h) * a.Wp + tid];
-        st_m[tid] = s.x;
-        st_rz[tid] = s.y;
-        st_cv[tid] = s.z;
-        st_ct[tid] = s.w;
-      }
-      __syncthreads();
-      if (hg == 0) frag_load(kf, ktile + (wave * 32 + n) * TL::kStride, kg);
+  // Heads are visited in order h = 0 .. Hq-1 (kv head g = h / G).  The tiles of head h+1 are fetched
+  // into registers while head h is processed out of LDS.
+  TileStage<T, D, kScoreTile> kstage;
+  TileStage<T, D, RB * 32> qstage;
+  float4 sreg = make_float4(0.f, 0.f, 0.f, 0.f);
+  const char* ktile_src = a.k + ((size_t)l * a.Hkv * a.T + j0) * TL::kRowBytes;
+  const size_t khead_stride = (size_t)a.T * TL::kRowBytes;
+  kstage.fetch(ktile_src, rows_valid, tid, 256);
+  qstage.fetch(a.q + (size_t)(l * a.Hq) * a.W * TL::kRowBytes, a.W, tid, 256);
+  if (tid < Wp) sreg = a.stats[(size_t)(l * a.Hq) * a.Wp + tid];
+
+  Frag<T, D> kf;
+  float colsum = 0.f;
+  for (int h = 0; h < a.Hq; ++h) {
+    const int g = h / a.G, hg = h - g * a.G;
+    __syncthreads();  // the previous head's tiles are no longer read
+    if (hg == 0) kstage.commit(ktile, tid, 256);
+    qstage.commit(qtile, tid, 256);
+    if (tid < Wp) {
+      st_m[tid] = sreg.x;
+      st_rz[tid] = sreg.y;
+      st_cv[tid] = sreg.z;
+      st_ct[tid] = sreg.w;
+    }
+    __syncthreads();
+    if (h + 1 < a.Hq) {
+      const int hn = h + 1;
+      if (hn % a.G == 0) kstage.fetch(ktile_src + (size_t)(hn / a.G) * khead_stride, rows_valid, tid, 256);
+      qstage.fetch(a.q + (size_t)(l * a.Hq + hn) * a.W * TL::kRowBytes, a.W, tid, 256);
+      if (tid < Wp) sreg = a.stats[(size_t)(l * a.Hq + hn) * a.Wp + tid];
+    }
+    if (hg == 0) {
+      frag_load(kf, ktile + (wave * 32 + n) * TL::kStride, kg);
+      colsum = 0.f;
+    }
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
-        Frag<T, D> qf;
-        frag_load(qf, qtile + (rb * 32 + n) * TL::kStride, kg);
-        f32x16_t acc = acc_zero();
-        mma<T, D>(acc, qf, kf);
+    for (int rb = 0; rb < RB; ++rb) {
+      Frag<T, D> qf;
+      frag_load(qf, qtile + (rb * 32 + n) * TL::kStride, kg);
+      f32x16_t acc = acc_zero();
+      mma<T, D>(acc, qf, kf);
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const int row0 = rb * 32 + r4 * 8 + kg * 4;  // rows of acc[r4*4 .. r4*4+3]
-          const float4 m4 = *reinterpret_cast<const float4*>(st_m + row0);
-          const float4 z4 = *reinterpret_cast<const float4*>(st_rz + row0);
-          const float4 c4 = *reinterpret_cast<const float4*>(st_coef + row0);
-          const float mm[4] = {m4.x, m4.y, m4.z, m4.w};
-          const float zz[4] = {z4.x, z4.y, z4.z, z4.w};
-          const float cc[4] = {c4.x, c4.y, c4.z, c4.w};
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int row0 = rb * 32 + r4 * 8 + kg * 4;  // rows of acc[r4*4 .. r4*4+3]
+        const float4 m4 = *reinterpret_cast<const float4*>(st_m + row0);
+        const float4 z4 = *reinterpret_cast<const float4*>(st_rz + row0);
+        const float4 c4 = *reinterpret_cast<const float4*>(st_coef + row0);
+        const float mm[4] = {m4.x, m4.y, m4.z, m4.w};
+        const float zz[4] = {z4.x, z4.y, z4.z, z4.w};
+        const float cc[4] = {c4.x, c4.y, c4.z, c4.w};
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            float e = fast_exp2(fmaf(acc[r4 * 4 + i], a.c, -mm[i]));
-            if (!full) {
-              const int row = row0 + i;
-              e = (col_ok && row < a.W && j <= a.T - a.W + row) ? e : 0.f;
-            }
-            colsum = fmaf(e, zz[i], colsum);
-            pbar[rb][r4 * 4 + i] = fmaf(e, cc[i], pbar[rb][r4 * 4 + i]);
+        for (int i = 0; i < 4; ++i) {
+          float e = fast_exp2(fmaf(acc[r4 * 4 + i], a.c, -mm[i]));
+          if (!full) {
+            const int row = row0 + i;
+            e = (col_ok && row < a.W && j <= a.T - a.W + row) ? e : 0.f;
           }
+          colsum = fmaf(e, zz[i], colsum);
+          pbar[rb][r4 * 4 + i] = fmaf(e, cc[i], pbar[rb][r4 * 4 + i]);
         }
       }
     }
-    colsum += __shfl_xor(colsum, 32, kWave);
-    if (kg == 0 && col_ok) a.col_scores[(size_t)(l * a.Hkv + g) * a.T + j] = colsum;
+    if (hg == a.G - 1) {
+      const float tot = colsum + __shfl_xor(colsum, 32, kWave);
+      if (kg == 0 && col_ok) a.col_scores[(size_t)(l * a.Hkv + g) * a.T + j] = tot;
+    }
   }
 
   // entropy terms of the head-averaged cross-modal probabilities.  A vision column only receives
@@ -329,7 +358,7 @@ static hipError_t launch_stats_t(const Plan& p, const ScoreArgs& a, hipStream_t 
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  dim3 grid(p.NCH, p.Hkv, p.L), block(p.NCG * p.CS * 64);
+  dim3 grid(p.NCH, p.Hkv, p.L), block((p.NCG * p.CS <= 4 ? 4 : 8) * 64);
   hipLaunchKernelGGL(kern, grid, block, lds, s, a);
   return hipGetLastError();
 }
