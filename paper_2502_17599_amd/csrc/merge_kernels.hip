@@ -307,6 +307,50 @@ __global__ void __launch_bounds__(kSortThreads) segment_sort_kernel(MergeArgs a)
 // so 64 lanes read 1024 bytes = several rows per step; sums are kept in fp64 (exact for the value
 // ranges of a KV cache, hence independent of the summation order) and rounded once to the
 // storage type.
+// sum / n for a positive integer n given rinv = fl(1/n): one multiply and one exact-remainder
+// correction.  When sum / n is representable the result is exactly that value, so ties of the final
+// rounding to the storage type fall the same way as with a true division.
+__device__ __forceinline__ double div_by_count(double sum, double n, double rinv) {
+  const double q0 = sum * rinv;
+  const double rem = fma(-q0, n, sum);
+  return fma(rem, rinv, q0);
+}
+
+// x + y exchanged between two lane groups O lanes apart: the lower group ends with its own x plus
+// the partner's x, the upper group with its own y plus the partner's y.
+template <int O>
+__device__ __forceinline__ double exchange_add(double x, double y, bool upper) {
+  if constexpr (O == 16 || O == 32) {
+    unsigned xl = (unsigned)__double2loint(x), xh = (unsigned)__double2hiint(x);
+    unsigned yl = (unsigned)__double2loint(y), yh = (unsigned)__double2hiint(y);
+    if constexpr (O == 32) {
+      const auto lo = __builtin_amdgcn_permlane32_swap(xl, yl, false, false);
+      const auto hi = __builtin_amdgcn_permlane32_swap(xh, yh, false, false);
+      xl = lo[0]; yl = lo[1]; xh = hi[0]; yh = hi[1];
+    } else {
+      const auto lo = __builtin_amdgcn_permlane16_swap(xl, yl, false, false);
+      const auto hi = __builtin_amdgcn_permlane16_swap(xh, yh, false, false);
+      xl = lo[0]; yl = lo[1]; xh = hi[0]; yh = hi[1];
+    }
+    return __hiloint2double((int)xh, (int)xl) + __hiloint2double((int)yh, (int)yl);
+  } else {
+    const double send = upper ? x : y, keep = upper ? y : x;
+    return keep + __shfl_xor(send, O, kWave);
+  }
+}
+
+// One halving step of the reduce-scatter over lane groups O lanes apart; returns the element offset
+// this lane moves to (LEN for the upper group).
+template <int LEN, int O, int E>
+__device__ __forceinline__ int reduce_scatter_step(double (&ak)[E], double (&av)[E], bool upper) {
+#pragma unroll
+  for (int i = 0; i < LEN; ++i) {
+    ak[i] = exchange_add<O>(ak[i], ak[i + LEN], upper);
+    av[i] = exchange_add<O>(av[i], av[i + LEN], upper);
+  }
+  return upper ? LEN : 0;
+}
+
 template <typename T>
 struct OutConv;
 template <>
@@ -322,14 +366,14 @@ struct OutConv<bf16_t> {
   }
   // store N consecutive elements sum[i] / denom, rounded once to bf16
   template <int N>
-  static __device__ __forceinline__ void store(char* dst, const double* sum, double denom) {
+  static __device__ __forceinline__ void store(char* dst, const double* sum, double denom, double rinv) {
     if constexpr (N == 1) {
-      *reinterpret_cast<uint16_t*>(dst) = (uint16_t)double_to_bf16_bits(sum[0] / denom);
+      *reinterpret_cast<uint16_t*>(dst) = (uint16_t)double_to_bf16_bits(div_by_count(sum[0], denom, rinv));
     } else {
 #pragma unroll
       for (int i = 0; i < N / 2; ++i)
-        reinterpret_cast<uint32_t*>(dst)[i] =
-            double_to_bf16_bits(sum[2 * i] / denom) | (double_to_bf16_bits(sum[2 * i + 1] / denom) << 16);
+        reinterpret_cast<uint32_t*>(dst)[i] = double_to_bf16_bits(div_by_count(sum[2 * i], denom, rinv)) |
+                                              (double_to_bf16_bits(div_by_count(sum[2 * i + 1], denom, rinv)) << 16);
     }
   }
 };
@@ -343,9 +387,9 @@ struct OutConv<float> {
     out[3] = (double)__uint_as_float(v.w);
   }
   template <int N>
-  static __device__ __forceinline__ void store(char* dst, const double* sum, double denom) {
+  static __device__ __forceinline__ void store(char* dst, const double* sum, double denom, double rinv) {
 #pragma unroll
-    for (int i = 0; i < N; ++i) reinterpret_cast<float*>(dst)[i] = __double2float_rn(sum[i] / denom);
+    for (int i = 0; i < N; ++i) reinterpret_cast<float*>(dst)[i] = __double2float_rn(div_by_count(sum[i], denom, rinv));
   }
 };
 
@@ -358,8 +402,10 @@ __global__ void __launch_bounds__(256) merge_write_kernel(MergeArgs a) {
   constexpr int E = CV::kElems;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const long long w = (long long)blockIdx.x * 4 + wave;
-  if (w >= a.total_slots) return;
+  // output rows are walked from the last layer to the first: the similarity kernel before this one
+  // touched the last layers' keys last
+  const long long w = a.total_slots - 1 - ((long long)blockIdx.x * 4 + wave);
+  if (w < 0) return;
   // everything the wave needs is indexed by its output row w: no layer / head lookup
   const int row0 = a.sel_idx[w];
   int m_beg = 0, m_end = 0;
@@ -430,29 +476,17 @@ __global__ void __launch_bounds__(256) merge_write_kernel(MergeArgs a) {
   // E / MS finished sums starting at element `ebase` of its 16-byte piece: the divisions and the
   // stores are spread over all 64 lanes.
   int ebase = 0;
-  {
-    int len = E;
-#pragma unroll
-    for (int step = 0; (LPR << step) < 64; ++step) {
-      len >>= 1;
-      const bool hi = (sub >> step) & 1;
-#pragma unroll
-      for (int i = 0; i < len; ++i) {
-        const double ks = hi ? ak[i] : ak[i + len], kk = hi ? ak[i + len] : ak[i];
-        const double vs = hi ? av[i] : av[i + len], vk = hi ? av[i + len] : av[i];
-        ak[i] = kk + __shfl_xor(ks, LPR << step, kWave);
-        av[i] = vk + __shfl_xor(vs, LPR << step, kWave);
-      }
-      ebase += hi ? len : 0;
-    }
-  }
+  if constexpr (MS >= 2) ebase += reduce_scatter_step<E / 2, LPR>(ak, av, (sub & 1) != 0);
+  if constexpr (MS >= 4) ebase += reduce_scatter_step<E / 4, 2 * LPR>(ak, av, (sub & 2) != 0);
+  if constexpr (MS >= 8) ebase += reduce_scatter_step<E / 8, 4 * LPR>(ak, av, (sub & 4) != 0);
   constexpr int EPL = E / MS;  // finished elements per lane
   static_assert(EPL >= 1, "a lane must end up with at least one element");
   const double denom = (double)n_rows;
+  const double rinv = 1.0 / denom;
   char* ko = a.k_out + (size_t)w * TL::kRowBytes + cc * 16 + ebase * (int)sizeof(T);
   char* vo = a.v_out + (size_t)w * TL::kRowBytes + cc * 16 + ebase * (int)sizeof(T);
-  CV::template store<EPL>(ko, ak, denom);
-  CV::template store<EPL>(vo, av, denom);
+  CV::template store<EPL>(ko, ak, denom, rinv);
+  CV::template store<EPL>(vo, av, denom, rinv);
 }
 
 // ------------------------------------------------------------------------------------------ launch

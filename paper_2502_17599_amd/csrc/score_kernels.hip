@@ -221,7 +221,9 @@ __global__ void __launch_bounds__(256) score_accum_kernel(ScoreArgs a) {
   float* st_ct = st_cv + RB * 32;
   double* red = reinterpret_cast<double*>(st_ct + RB * 32);  // [4][2]
 
-  const int tile = blockIdx.x, l = blockIdx.y;
+  // layers are walked in the opposite order of pass A, so the keys pass A touched last (still in the
+  // memory-side cache) are the first ones read here
+  const int tile = blockIdx.x, l = a.L - 1 - blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, kg = lane >> 5;
   const int j0 = tile * kScoreTile;
   const int j = j0 + wave * 32 + n;  // this lane's key column
