@@ -34,7 +34,8 @@ class MedaParams(ctypes.Structure):
 
 
 def library_path() -> str:
-    return os.path.join(_PKG_DIR, _LIB_NAME)
+    """The built library next to this file, or the file named by the MEDA_LIBRARY environment variable."""
+    return os.environ.get("MEDA_LIBRARY") or os.path.join(_PKG_DIR, _LIB_NAME)
 
 
 _lib = None

@@ -50,33 +50,53 @@ __device__ __forceinline__ int sort_passes(int S) {
 // (double buffered: the global loads of tile t+1 and the position loads of tile t+2 are in flight
 // while tile t is multiplied).  With the conserved keys as operand A, a lane owns ONE row and sees
 // 16 candidate slots per 32x32 block in its 16 accumulator registers: the running best of the row is
-// a single (value, slot) pair per lane, the block maximum is a max3 tree, and the search for the slot
-// that reached it only runs in blocks where some lane of the wave improved.
+// one value per lane and the block maximum is a max3 tree (see RowBest).
+// Running best of one row (one lane) over the blocks it has seen: the best value, the first slot of
+// the block that produced it and that block's 16 scaled products.  Keeping the products postpones the
+// search for the winning register to the end of the kernel: per block only the maximum is formed
+// (max3 tree), and the 16 products are copied in blocks where some lane of the wave improved.
+struct RowBest {
+  float best;
+  int slot0;
+  float u[16];
+};
+
 template <bool TAIL>
 __device__ __forceinline__ void argmax_block(const f32x16_t& acc, const float (&iv)[16], int slot0, int kg, int S,
-                                             float& best, int& bidx) {
+                                             RowBest& rb) {
   float u[16];
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     u[r] = acc[r] * iv[r];
     if (TAIL) u[r] = (slot0 + acc_row(r, kg) < S) ? u[r] : -INFINITY;
   }
-  float bm = fmaxf(u[0], u[1]);
+  float bm = fmaxf(fmaxf(u[0], u[1]), u[2]);
 #pragma unroll
-  for (int r = 2; r < 16; r += 2) bm = fmaxf(bm, fmaxf(u[r], u[r + 1]));
-  const bool improved = bm > best;
+  for (int r = 3; r < 15; r += 2) bm = fmaxf(fmaxf(bm, u[r]), u[r + 1]);
+  bm = fmaxf(bm, u[15]);
+  const bool improved = bm > rb.best;  // strict: an equal value in a later block does not replace
   if (__ballot(improved) != 0ull) {
-    int ridx = 15;
 #pragma unroll
-    for (int r = 14; r >= 0; --r) ridx = (u[r] != bm) ? ridx : r;  // lowest register that holds the maximum
-    best = improved ? bm : best;
-    bidx = improved ? slot0 + acc_row(ridx, kg) : bidx;
+    for (int r = 0; r < 16; ++r) rb.u[r] = improved ? u[r] : rb.u[r];
+    rb.best = improved ? bm : rb.best;
+    rb.slot0 = improved ? slot0 : rb.slot0;
   }
+}
+
+// Slot of the row's best: the lowest register of the saved block that holds the maximum.
+// best - u[r] is +0 exactly there and positive elsewhere, and the bit patterns of non-negative floats
+// order like unsigned integers, so the minimum of (bits << 4 | r) carries r of the first maximum.
+__device__ __forceinline__ int row_best_slot(const RowBest& rb, int kg) {
+  unsigned key = 0xffffffffu;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) key = min(key, (__float_as_uint(rb.best - rb.u[r]) << 4) | (unsigned)r);
+  const int ridx = (int)(key & 15u);
+  return rb.slot0 + (ridx >> 2) * 8 + kg * 4 + (ridx & 3);
 }
 
 template <typename T, int D, bool TAIL>
 __device__ __forceinline__ void sim_tile(const char* ctile, const float* cinv, int s0, int S, int n, int kg,
-                                         const Frag<T, D> (&lf)[2], float (&best)[2], int (&bidx)[2]) {
+                                         const Frag<T, D> (&lf)[2], RowBest (&rb)[2]) {
   using TL = Tile<T, D>;
 #pragma unroll
   for (int cb = 0; cb < kSimSlotTile / 32; ++cb) {
@@ -95,8 +115,8 @@ __device__ __forceinline__ void sim_tile(const char* ctile, const float* cinv, i
     f32x16_t acc0 = acc_zero(), acc1 = acc_zero();
     mma<T, D>(acc0, cf, lf[0]);
     mma<T, D>(acc1, cf, lf[1]);
-    argmax_block<TAIL>(acc0, iv, s0 + cb * 32, kg, S, best[0], bidx[0]);
-    argmax_block<TAIL>(acc1, iv, s0 + cb * 32, kg, S, best[1], bidx[1]);
+    argmax_block<TAIL>(acc0, iv, s0 + cb * 32, kg, S, rb[0]);
+    argmax_block<TAIL>(acc1, iv, s0 + cb * 32, kg, S, rb[1]);
   }
 }
 
@@ -136,8 +156,14 @@ __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 
     else
       frag_zero(lf[s]);
   }
-  float best[2] = {-INFINITY, -INFINITY};
-  int bidx[2] = {0, 0};
+  RowBest rb[2];
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    rb[s].best = -INFINITY;
+    rb[s].slot0 = 0;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) rb[s].u[r] = -INFINITY;
+  }
 
   // this thread's pieces of a tile: piece i is 16 bytes at row prow0 + i * ROWS_PER_PIECE_STEP, column pcc
   const int prow0 = tid / CPR, pcc = tid - prow0 * CPR;
@@ -175,9 +201,9 @@ __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 
       if (t + 2 < ntiles) { MEDA_SIM_LOAD_IDX(t + 2) }
     }
     if (t < nfull)
-      sim_tile<T, D, false>(ctile[t & 1], cinv[t & 1], t * kSimSlotTile, S, n, kg, lf, best, bidx);
+      sim_tile<T, D, false>(ctile[t & 1], cinv[t & 1], t * kSimSlotTile, S, n, kg, lf, rb);
     else
-      sim_tile<T, D, true>(ctile[t & 1], cinv[t & 1], t * kSimSlotTile, S, n, kg, lf, best, bidx);
+      sim_tile<T, D, true>(ctile[t & 1], cinv[t & 1], t * kSimSlotTile, S, n, kg, lf, rb);
     if (t + 1 < ntiles) { MEDA_SIM_COMMIT((t + 1) & 1) }
   }
 #undef MEDA_SIM_LOAD_IDX
@@ -187,10 +213,11 @@ __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 
   // the two lane groups saw disjoint slots of the same row: keep the better, ties -> lower slot
 #pragma unroll
   for (int s = 0; s < 2; ++s) {
-    const float ov = __shfl_xor(best[s], 32, kWave);
-    const int oi = __shfl_xor(bidx[s], 32, kWave);
-    const bool take = ov > best[s] || (ov == best[s] && oi < bidx[s]);
-    const int bi = take ? oi : bidx[s];
+    const int mine = row_best_slot(rb[s], kg);
+    const float ov = __shfl_xor(rb[s].best, 32, kWave);
+    const int oi = __shfl_xor(mine, 32, kWave);
+    const bool take = ov > rb[s].best || (ov == rb[s].best && oi < mine);
+    const int bi = take ? oi : mine;
     const int ri = r0 + s * 32 + n;
     if (kg == 0 && ri < n_less) {
       a.less_slot[lbase + ri] = bi;
