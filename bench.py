@@ -43,6 +43,22 @@ def algorithmic_work(wl, budgets):
     }
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of ``kernel`` from the committed rocprofv3 counter summary of this workload
+    (FETCH_SIZE and WRITE_SIZE, already scaled by the plain-copy calibration), or None."""
+    path = os.path.join(ROOT, "profiles", f"hbm_counters_{workload}.md")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 4 and cells[0] == kernel:
+            try:
+                return float(cells[1]) + float(cells[2])
+            except ValueError:
+                return None
+    return None
+
+
 def cpu_baseline(wl, seconds_target=20.0):
     """The fp64 oracle on a bounded sample: the first n layers of the same workload with the budget
     scaled to n layers, n chosen from a one-layer probe so the run takes roughly ``seconds_target``."""
@@ -146,7 +162,8 @@ def main():
         else:
             achieved, peak, unit = work[dom] / t_s / 1e9, HBM_PEAK_GBS, "GB/s"
         roofline = {"kernel": dom, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                    "frac": achieved / peak, "traffic": None, "kernel_ms": per_phase[dom]}
+                    "frac": achieved / peak, "traffic": measured_traffic(wl.name, dom),
+                    "kernel_ms": per_phase[dom]}
 
     e = 2 if wl.dtype == "bf16" else 4
     alg_bytes = work["merge_write"]        # K and V once + the output: the traffic of the whole pass

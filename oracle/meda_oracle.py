@@ -285,6 +285,9 @@ def boosted_scores(a_s: np.ndarray, mask: np.ndarray) -> np.ndarray:
 # Step 5: nearest conserved key
 # --------------------------------------------------------------------------------------
 
+TIE_EPS = 1e-12   # float64 rounding noise of a 128-term cosine is ~1e-16; real gaps are >> 1e-12
+
+
 def cosine_matrix(k_less: np.ndarray, k_c: np.ndarray) -> np.ndarray:
     """u[i, j] = k_i . k_j / (|k_i| |k_j|) (Section 3.3); a zero key has its norm guarded."""
     a = np.asarray(k_less, dtype=F64)
@@ -300,7 +303,10 @@ def nn_assign(k: np.ndarray, idx_c: np.ndarray, idx_less: np.ndarray, chunk: int
 
     k [T, d] keys of one (layer, kv head) -- the original, un-merged keys: one similarity
     matrix is formed and all merges happen at once.  Targets are all conserved slots (Top-N
-    and recent).  Equal similarities resolve to the lower slot.  Returns assign int64
+    and recent).  Equal similarities resolve to the lower slot; "equal" means equal as real
+    numbers, so similarities within ``TIE_EPS`` of the row maximum (the rounding noise of a
+    float64 matrix product, which can differ between two identical conserved keys) count as
+    equal.  Returns assign int64
     [len(idx_less)] of slot numbers in [0, len(idx_c)); with ``return_margin`` also the best
     similarity and the gap to the runner-up slot (inf when there is one slot).
     """
@@ -312,7 +318,7 @@ def nn_assign(k: np.ndarray, idx_c: np.ndarray, idx_less: np.ndarray, chunk: int
     gap = np.full(n, np.inf, dtype=F64)
     for a in range(0, n, chunk):
         u = cosine_matrix(k[idx_less[a:a + chunk]], k_c)
-        j = np.argmax(u, axis=1)                      # first maximum = lowest slot
+        j = np.argmax(u >= u.max(axis=1, keepdims=True) - TIE_EPS, axis=1)   # first maximum = lowest slot
         assign[a:a + chunk] = j
         if return_margin:
             rows = np.arange(u.shape[0])
@@ -320,7 +326,7 @@ def nn_assign(k: np.ndarray, idx_c: np.ndarray, idx_less: np.ndarray, chunk: int
             best[a:a + chunk] = top
             if u.shape[1] > 1:
                 u[rows, j] = -np.inf
-                gap[a:a + chunk] = top - u.max(axis=1)
+                gap[a:a + chunk] = np.maximum(top - u.max(axis=1), 0.0)
     if return_margin:
         return assign, best, gap
     return assign

@@ -120,6 +120,27 @@ def test_duplicate_of_a_conserved_key_maps_to_its_lowest_copy():
     assert got[list(idx_less).index(9)] == 1     # slot of position 3, the lower of the duplicates
 
 
+def test_identical_conserved_keys_always_resolve_to_the_lowest_slot():
+    # many columns and rows, so that a blocked float64 matrix product rounds identical columns differently:
+    # the tie rule must not depend on that noise
+    r = rng(8)
+    T, d = 900, 64
+    k = r.standard_normal((T, d)).astype(np.float32).astype(np.float64)
+    heavy = 3.0 * k[5] / np.linalg.norm(k[5])
+    dup_pos = [7, 130, 131, 395, 640]
+    k[dup_pos] = heavy
+    idx_c = np.array(sorted(set(range(0, T, 3)) | set(dup_pos)))
+    idx_less = np.array([t for t in range(T) if t not in set(idx_c)])
+    k[idx_less[::4]] = heavy * r.uniform(0.5, 2.0, size=(len(idx_less[::4]), 1))   # rows whose best is the duplicate
+    got = O.nn_assign(k, idx_c, idx_less, chunk=257)
+    lowest = int(np.flatnonzero(idx_c == 7)[0])
+    assert np.all(got[::4] == lowest)
+    # brute force on a sample of the other rows
+    for n in range(1, len(idx_less), 37):
+        u = [float(np.dot(k[idx_less[n]], k[j]) / (np.linalg.norm(k[idx_less[n]]) * np.linalg.norm(k[j]))) for j in idx_c]
+        assert abs(u[got[n]] - max(u)) <= 1e-12
+
+
 def test_margin_reporting():
     k = np.array([[1.0, 0.0], [0.0, 1.0], [1.0, 0.1]])
     a, best, gap = O.nn_assign(k, np.array([0, 1]), np.array([2]), return_margin=True)
