@@ -141,6 +141,43 @@ def test_identical_conserved_keys_always_resolve_to_the_lowest_slot():
         assert abs(u[got[n]] - max(u)) <= 1e-12
 
 
+def test_heavy_hitter_duplicates_in_a_workload_resolve_to_the_lowest_slot():
+    # the workloads hold exact duplicate keys (heavy hitters): whatever slot a row is assigned to, no
+    # lower conserved slot may hold a bit-identical key (fails with a plain argmax over the float64 product)
+    wl = variant(get_workload("tiny"), tau_lo=1.5, tau_hi=1.5, n_layers=3, total_budget=700)
+    d = generate(wl)
+    res = O.meda_compress(to_float64(d["q"]), to_float64(d["k"]), to_float64(d["v"]), d["mask"].numpy(),
+                          wl.total_budget, wl.window, wl.dtype)
+    k = to_float64(d["k"])[0]
+    n_dup_rows = 0
+    for g, h in enumerate(res["heads"][0]):
+        kc = k[g][h["idx_c"]]
+        _, first = np.unique(kc, axis=0, return_index=True)
+        lowest_copy = {kc[i].tobytes(): i for i in sorted(first, reverse=True)}
+        for i in sorted(first):
+            lowest_copy[kc[i].tobytes()] = min(lowest_copy[kc[i].tobytes()], i)
+        canon = np.array([lowest_copy[row.tobytes()] for row in kc])
+        n_dup_rows += int((canon[h["assign"]] != np.arange(len(kc))[h["assign"]]).sum())
+        assert np.array_equal(canon[h["assign"]], h["assign"])
+    assert n_dup_rows == 0
+
+
+def test_rounding_noise_between_equal_similarities_does_not_pick_a_higher_slot(monkeypatch):
+    # emulate a matrix product that rounds two identical columns differently by one unit in the last place
+    k = np.array([[1.0, 2.0], [3.0, 1.0], [1.0, 2.0], [0.5, 1.0], [-1.0, 0.3]])
+    exact = O.cosine_matrix
+
+    def noisy(a, b):
+        u = exact(a, b)
+        u[:, 0] -= 2.3e-16          # column 0 and column 2 are the same key; make the lower one look smaller
+        return u
+    monkeypatch.setattr(O, "cosine_matrix", noisy)
+    got = O.nn_assign(k, np.array([0, 1, 2]), np.array([3, 4]))
+    assert got[0] == 0              # [0.5, 1] is parallel to slots 0 and 2: the lower slot wins
+    # a real gap far above the noise is still respected
+    assert got[1] == int(np.argmax(exact(k[[4]], k[[0, 1, 2]])[0]))
+
+
 def test_margin_reporting():
     k = np.array([[1.0, 0.0], [0.0, 1.0], [1.0, 0.1]])
     a, best, gap = O.nn_assign(k, np.array([0, 1]), np.array([2]), return_margin=True)
