@@ -33,10 +33,10 @@ __device__ __forceinline__ size_t less_base_of(int l, int g, int T, int Hkv, lon
   return ((size_t)l * T - (size_t)off_l) * Hkv + (size_t)g * (T - S);
 }
 
-// number of 4-bit passes the segment sort needs for slots in [0, S)
+// number of 5-bit passes the segment sort needs for slots in [0, S)
 __device__ __forceinline__ int sort_passes(int S) {
   const int nbits = (S > 1) ? (32 - __clz(S - 1)) : 1;
-  return (nbits + 3) / 4;
+  return (nbits + 4) / 5;
 }
 
 // ------------------------------------------------------------------------ similarity + argmax
@@ -227,18 +227,37 @@ __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 
 }
 
 // ------------------------------------------------------------------------------- segment sort
-// grid (Hkv, L); 1024 threads.  Stable least-significant-digit radix sort (4 bits per pass) of the
-// pairs (slot, row id) of one (layer, head) by slot; row ids enter ascending, so every slot's
-// members come out ascending and the merge adds them in one fixed order.  The last pass always
-// writes buffer 0.  Then seg_beg / seg_end of every slot = its range in the sorted array.
-constexpr int kSortThreads = 1024;
-constexpr int kSortWaves = kSortThreads / 64;
+// grid (Hkv, L).  Stable least-significant-digit radix sort (5 bits per pass) of the pairs
+// (slot, row id) of one (layer, head) by slot; row ids enter ascending, so every slot's members come
+// out ascending and the merge adds them in one fixed order.  The last pass always writes buffer 0.
+// Per tile of blockDim elements: a lane finds the lanes of its wave with the same digit (one ballot
+// per digit bit) and its rank among them, the per-wave digit counts go to LDS, wave 0 turns them into exclusive prefixes over the
+// waves (and advances the running digit bases), and every element is written to its final place.
+// Then seg_beg / seg_end of every slot = its range in the sorted array.
+constexpr int kSortMaxThreads = 1024;
+constexpr int kSortMaxWaves = kSortMaxThreads / 64;
+constexpr int kSortBits = 5;
+constexpr int kSortDigits = 1 << kSortBits;
+constexpr int kSortItems = 4;  // tiles whose loads are issued together
 
-__global__ void __launch_bounds__(kSortThreads) segment_sort_kernel(MergeArgs a) {
-  __shared__ int base[16];
-  __shared__ int wcnt[kSortWaves][16];
+// Lanes of the wave whose 5-bit digit equals this lane's (invalid lanes match nobody): one ballot per
+// digit bit, each lane keeps the side of the ballot it is on.
+__device__ __forceinline__ unsigned long long digit_peers(int dgt, bool valid) {
+  unsigned long long peers = __ballot(valid);
+#pragma unroll
+  for (int b = 0; b < kSortBits; ++b) {
+    const unsigned long long set = __ballot((dgt >> b) & 1);
+    peers &= ((dgt >> b) & 1) ? set : ~set;
+  }
+  return valid ? peers : 0ull;
+}
+
+__global__ void __launch_bounds__(kSortMaxThreads, 8) segment_sort_kernel(MergeArgs a) {
+  __shared__ int base[2][kSortDigits];
+  __shared__ int wcnt[2][kSortMaxWaves][kSortDigits];
 
   const int g = blockIdx.x, l = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nthr = blockDim.x, nwaves = nthr >> 6;
   const int S = a.alloc[4 * l];
   const int n = a.T - S;
   const long long off_l = a.off[l];
@@ -252,62 +271,91 @@ __global__ void __launch_bounds__(kSortThreads) segment_sort_kernel(MergeArgs a)
     const int ob = (passes - 1 - p) & 1;
     int32_t* out_key = a.sort_key[ob] + lbase;
     int32_t* out_val = a.sort_val[ob] + lbase;
-    const int shift = 4 * p;
-    if (tid < 16) base[tid] = 0;
+    const int shift = kSortBits * p;
+    if (tid < kSortDigits) base[0][tid] = 0;
     __syncthreads();
-    // digit histogram
-    int mine[16];
+    // digit histogram: lane q of every wave counts digit q.  Four tiles are loaded at a time so
+    // that their loads are in flight together.
+    for (int t0 = 0; t0 < n; t0 += kSortItems * nthr) {
+      int keys[kSortItems];
 #pragma unroll
-    for (int q = 0; q < 16; ++q) mine[q] = 0;
-    for (int t0 = 0; t0 < n; t0 += kSortThreads) {
-      const int i = t0 + tid;
-      const int dgt = (i < n) ? ((in_key[i] >> shift) & 15) : 16;
+      for (int j = 0; j < kSortItems; ++j) {
+        const int i = t0 + j * nthr + tid;
+        keys[j] = (i < n) ? in_key[i] : -1;
+      }
 #pragma unroll
-      for (int q = 0; q < 16; ++q) mine[q] += __popcll(__ballot(dgt == q));
-    }
-    if (lane == 0) {
-#pragma unroll
-      for (int q = 0; q < 16; ++q) atomicAdd(&base[q], mine[q]);
-    }
-    __syncthreads();
-    if (tid == 0) {
-      int run = 0;
-      for (int q = 0; q < 16; ++q) {
-        const int c = base[q];
-        base[q] = run;
-        run += c;
+      for (int j = 0; j < kSortItems; ++j) {
+        if (t0 + j * nthr < n) {
+          const bool valid = keys[j] >= 0;
+          const int dgt = (keys[j] >> shift) & (kSortDigits - 1);
+          const unsigned long long peers = digit_peers(dgt, valid);
+          if (valid && (peers & lt_mask) == 0ull) atomicAdd(&base[0][dgt], __popcll(peers));  // group leader
+        }
       }
     }
     __syncthreads();
-    // stable scatter, 1024 elements at a time in input order
-    for (int t0 = 0; t0 < n; t0 += kSortThreads) {
-      const int i = t0 + tid;
-      const bool valid = i < n;
-      const int key = valid ? in_key[i] : 0;
-      const int val = valid ? in_val[i] : 0;
-      const int dgt = valid ? ((key >> shift) & 15) : 16;
-      int my_rank = 0;
+    if (wave == 0) {  // exclusive scan of the 32 digit totals
+      const int c = (lane < kSortDigits) ? base[0][lane] : 0;
+      int inc = c;
 #pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const unsigned long long b = __ballot(dgt == q);
-        if (dgt == q) my_rank = __popcll(b & lt_mask);
-        if (lane == q) wcnt[wave][q] = __popcll(b);
+      for (int o = 1; o < kSortDigits; o <<= 1) {
+        const int t = __shfl_up(inc, o, kWave);
+        if (lane >= o) inc += t;
       }
-      __syncthreads();
-      if (valid) {
-        int pos = base[dgt] + my_rank;
-        for (int w2 = 0; w2 < wave; ++w2) pos += wcnt[w2][dgt];
-        out_key[pos] = key;
-        out_val[pos] = val;
-      }
-      __syncthreads();
-      if (tid < 16) {
-        int tot = 0;
-        for (int w2 = 0; w2 < kSortWaves; ++w2) tot += wcnt[w2][tid];
-        base[tid] += tot;
-      }
-      __syncthreads();
+      if (lane < kSortDigits) base[0][lane] = inc - c;
     }
+    __syncthreads();
+    // stable scatter, blockDim elements at a time in input order (loads of four tiles in flight)
+    int it = 0;
+    for (int s0 = 0; s0 < n; s0 += kSortItems * nthr) {
+      int keys[kSortItems], vals[kSortItems];
+#pragma unroll
+      for (int j = 0; j < kSortItems; ++j) {
+        const int i = s0 + j * nthr + tid;
+        keys[j] = (i < n) ? in_key[i] : -1;
+        vals[j] = (i < n) ? in_val[i] : 0;
+      }
+#pragma unroll
+      for (int j = 0; j < kSortItems; ++j) {
+        if (s0 + j * nthr < n) {
+          const int cur = it & 1;
+          ++it;
+          const int key = keys[j], val = vals[j];
+          const bool valid = key >= 0;
+          const int dgt = (key >> shift) & (kSortDigits - 1);
+          const unsigned long long peers = digit_peers(dgt, valid);
+          const int my_rank = __popcll(peers & lt_mask);
+          if (lane < kSortDigits) wcnt[cur][wave][lane] = 0;
+          if (valid && my_rank == 0) wcnt[cur][wave][dgt] = __popcll(peers);  // after the zeroing: same wave, in order
+          __syncthreads();
+          if (wave == 0) {
+            // lane (q, half): digit q = lane / 2, waves half*8 .. half*8+7; exclusive prefix over the waves
+            const int q = lane >> 1, w0 = (lane & 1) * (kSortMaxWaves / 2);
+            int run = 0, c[kSortMaxWaves / 2];
+#pragma unroll
+            for (int w2 = 0; w2 < kSortMaxWaves / 2; ++w2) {
+              c[w2] = (w0 + w2 < nwaves) ? wcnt[cur][w0 + w2][q] : 0;
+              run += c[w2];
+            }
+            const int other = __shfl_xor(run, 1, kWave);
+            int pre = (lane & 1) ? other : 0;  // counts of the lower half of the waves
+#pragma unroll
+            for (int w2 = 0; w2 < kSortMaxWaves / 2; ++w2) {
+              if (w0 + w2 < nwaves) wcnt[cur][w0 + w2][q] = pre;
+              pre += c[w2];
+            }
+            if ((lane & 1) == 0) base[cur ^ 1][q] = base[cur][q] + run + other;
+          }
+          __syncthreads();
+          if (valid) {
+            const int pos = base[cur][dgt] + wcnt[cur][wave][dgt] + my_rank;
+            out_key[pos] = key;
+            out_val[pos] = val;
+          }
+        }
+      }
+    }
+    __syncthreads();
     in_key = out_key;
     in_val = out_val;
   }
@@ -317,15 +365,15 @@ __global__ void __launch_bounds__(kSortThreads) segment_sort_kernel(MergeArgs a)
   int32_t* beg = a.seg_beg + cbase;
   int32_t* end = a.seg_end + cbase;
   const int ib = (int)lbase;
-  for (int i = tid; i < n; i += kSortThreads) {
+  for (int i = tid; i < n; i += nthr) {
     const int kcur = in_key[i];
     const int kprev = (i > 0) ? in_key[i - 1] : -1;
     for (int s = kprev + 1; s <= kcur; ++s) beg[s] = ib + i;
     for (int s = max(kprev, 0); s < kcur; ++s) end[s] = ib + i;
   }
   const int klast = (n > 0) ? in_key[n - 1] : -1;
-  for (int s = klast + 1 + tid; s < S; s += kSortThreads) beg[s] = ib + n;
-  for (int s = max(klast, 0) + tid; s < S; s += kSortThreads) end[s] = ib + n;
+  for (int s = klast + 1 + tid; s < S; s += nthr) beg[s] = ib + n;
+  for (int s = max(klast, 0) + tid; s < S; s += nthr) end[s] = ib + n;
 }
 
 // ------------------------------------------------------------------------------ merge + write
@@ -559,7 +607,8 @@ hipError_t launch_similarity(const Plan& p, const Buffers& b, hipStream_t s) {
 
 hipError_t launch_segment_sort(const Plan& p, const Buffers& b, hipStream_t s) {
   const MergeArgs a = make_args(p, b);
-  hipLaunchKernelGGL(segment_sort_kernel, dim3(p.Hkv, p.L), dim3(kSortThreads), 0, s, a);
+  const int nthr = p.T >= 4096 ? 1024 : 256;
+  hipLaunchKernelGGL(segment_sort_kernel, dim3(p.Hkv, p.L), dim3(nthr), 0, s, a);
   return hipGetLastError();
 }
 
