@@ -61,15 +61,10 @@ struct RowBest {
   float u[16];
 };
 
-template <bool TAIL>
-__device__ __forceinline__ void argmax_block(const f32x16_t& acc, const float (&iv)[16], int slot0, int kg, int S,
-                                             RowBest& rb) {
+__device__ __forceinline__ void argmax_block(const f32x16_t& acc, const float (&iv)[16], int slot0, RowBest& rb) {
   float u[16];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    u[r] = acc[r] * iv[r];
-    if (TAIL) u[r] = (slot0 + acc_row(r, kg) < S) ? u[r] : -INFINITY;
-  }
+  for (int r = 0; r < 16; ++r) u[r] = acc[r] * iv[r];
   float bm = fmaxf(fmaxf(u[0], u[1]), u[2]);
 #pragma unroll
   for (int r = 3; r < 15; r += 2) bm = fmaxf(fmaxf(bm, u[r]), u[r + 1]);
@@ -94,13 +89,16 @@ __device__ __forceinline__ int row_best_slot(const RowBest& rb, int kg) {
   return rb.slot0 + (ridx >> 2) * 8 + kg * 4 + (ridx & 3);
 }
 
-template <typename T, int D, bool TAIL>
-__device__ __forceinline__ void sim_tile(const char* ctile, const float* cinv, int s0, int S, int n, int kg,
+// One LDS tile of conserved keys against the wave's two row fragments.  The last tile of a (layer,
+// head) is padded with copies of the last conserved key: a copy ties with the original and the tie
+// rules (strict improvement, lowest register, lower slot between the lane groups) always prefer the
+// original, so no slot needs masking and there is a single code path.
+template <typename T, int D>
+__device__ __forceinline__ void sim_tile(const char* ctile, const float* cinv, int s0, int n, int kg,
                                          const Frag<T, D> (&lf)[2], RowBest (&rb)[2]) {
   using TL = Tile<T, D>;
 #pragma unroll
   for (int cb = 0; cb < kSimSlotTile / 32; ++cb) {
-    if (TAIL && s0 + cb * 32 >= S) break;
     Frag<T, D> cf;
     frag_load(cf, ctile + (cb * 32 + n) * TL::kStride, kg);
     float iv[16];
@@ -115,8 +113,8 @@ __device__ __forceinline__ void sim_tile(const char* ctile, const float* cinv, i
     f32x16_t acc0 = acc_zero(), acc1 = acc_zero();
     mma<T, D>(acc0, cf, lf[0]);
     mma<T, D>(acc1, cf, lf[1]);
-    argmax_block<TAIL>(acc0, iv, s0 + cb * 32, kg, S, rb[0]);
-    argmax_block<TAIL>(acc1, iv, s0 + cb * 32, kg, S, rb[1]);
+    argmax_block(acc0, iv, s0 + cb * 32, rb[0]);
+    argmax_block(acc1, iv, s0 + cb * 32, rb[1]);
   }
 }
 
@@ -169,22 +167,21 @@ __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 
   const int prow0 = tid / CPR, pcc = tid - prow0 * CPR;
   int pidx[PF];
   uint4 pre[PF];
+#pragma unroll
+  for (int i = 0; i < PF; ++i) pre[i] = make_uint4(0, 0, 0, 0);
   float piv = 0.f;
   const int ntiles = (S + kSimSlotTile - 1) / kSimSlotTile;
-  const int nfull = S / kSimSlotTile;
 
 #define MEDA_SIM_LOAD_IDX(t)                                                      \
   _Pragma("unroll") for (int i = 0; i < PF; ++i) {                                \
     const int slot = (t) * kSimSlotTile + prow0 + i * ROWS_PER_PIECE_STEP;        \
-    pidx[i] = (slot < S) ? cidx[slot] : -1;                                       \
+    pidx[i] = cidx[min(slot, S - 1)];                                             \
   }
 #define MEDA_SIM_ISSUE(t)                                                                                \
   _Pragma("unroll") for (int i = 0; i < PF; ++i) {                                                       \
-    pre[i] = make_uint4(0, 0, 0, 0);                                                                     \
-    if (pidx[i] >= 0)                                                                                    \
-      pre[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)pidx[i] * TL::kRowBytes + pcc * 16);      \
+    pre[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)pidx[i] * TL::kRowBytes + pcc * 16);        \
   }                                                                                                      \
-  if (tid < kSimSlotTile) piv = ((t) * kSimSlotTile + tid < S) ? sinv[(t) * kSimSlotTile + tid] : 0.f;
+  if (tid < kSimSlotTile) piv = sinv[min((t) * kSimSlotTile + tid, S - 1)];
 #define MEDA_SIM_COMMIT(buf)                                                                             \
   _Pragma("unroll") for (int i = 0; i < PF; ++i)                                                         \
     *reinterpret_cast<uint4*>(ctile[buf] + (prow0 + i * ROWS_PER_PIECE_STEP) * TL::kStride + pcc * 16) = pre[i]; \
@@ -200,10 +197,7 @@ __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 
       MEDA_SIM_ISSUE(t + 1)
       if (t + 2 < ntiles) { MEDA_SIM_LOAD_IDX(t + 2) }
     }
-    if (t < nfull)
-      sim_tile<T, D, false>(ctile[t & 1], cinv[t & 1], t * kSimSlotTile, S, n, kg, lf, rb);
-    else
-      sim_tile<T, D, true>(ctile[t & 1], cinv[t & 1], t * kSimSlotTile, S, n, kg, lf, rb);
+    sim_tile<T, D>(ctile[t & 1], cinv[t & 1], t * kSimSlotTile, n, kg, lf, rb);
     if (t + 1 < ntiles) { MEDA_SIM_COMMIT((t + 1) & 1) }
   }
 #undef MEDA_SIM_LOAD_IDX
