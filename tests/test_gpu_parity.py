@@ -91,3 +91,45 @@ def test_deterministic_across_runs():
     _, b = run_gpu(wl, data)
     for key in ("k_out", "v_out", "sel_idx", "merge_assign", "entropy", "col_scores"):
         assert np.array_equal(a[key], b[key]), key
+
+
+def test_flag_uniform_budget_ignores_the_entropies():
+    # ablation "without dynamic allocation" (Table 5 of the paper): every layer gets B/L, extras on the lowest layers
+    import paper_2502_17599_amd as pkg
+    from oracle import meda_oracle as O
+    wl = variant(TINY, name="uniform_budget", n_layers=3, total_budget=3 * 200 + 2)
+    data = generate(wl)
+    comp, gpu = run_gpu(wl, data, flags=pkg.FLAG_UNIFORM_BUDGET)
+    S, M, N, off = O.allocate_budgets(np.zeros(wl.n_layers), wl.total_budget, wl.seq_len, wl.window,
+                                      wl.recent_num, wl.recent_den)
+    assert gpu["S"].tolist() == S.tolist() == [201, 201, 200]
+    assert np.array_equal(gpu["alloc"][:, 1], M) and np.array_equal(gpu["alloc"][:, 2], N)
+    # downstream stages still match the oracle run with these budgets
+    from parity import check_head, oracle_scores
+    a_s, _ = oracle_scores(wl, data)
+    stats = {"heads": 0, "rows": 0, "ambiguous_rows": 0, "sets_differing_in_tie_band": 0,
+             "max_kv_err": 0.0, "kv_elems_not_bit_exact": 0}
+    for l in range(wl.n_layers):
+        for g in range(wl.n_kv_heads):
+            check_head(wl, data, gpu, a_s[l], l, g, int(N[l]), int(M[l]), stats)
+    assert stats["kv_elems_not_bit_exact"] == 0
+
+
+def test_flag_no_merge_copies_the_conserved_rows():
+    # ablation "without average merging": eviction, the kept rows are bit-exact copies
+    import paper_2502_17599_amd as pkg
+    from parity import gpu_head
+    wl = variant(TINY, name="no_merge")
+    data = generate(wl)
+    comp, ref = run_gpu(wl, data)
+    comp, gpu = run_gpu(wl, data, flags=pkg.FLAG_NO_MERGE)
+    assert np.array_equal(gpu["S"], ref["S"]) and np.array_equal(gpu["sel_idx"], ref["sel_idx"])
+    k = data["k"].to(torch.float64).numpy(); v = data["v"].to(torch.float64).numpy()
+    for l in range(wl.n_layers):
+        for g in range(wl.n_kv_heads):
+            idx, k_out, v_out = gpu_head(wl, gpu, l, g)
+            assert np.array_equal(k_out, k[l, g][idx]) and np.array_equal(v_out, v[l, g][idx])
+            ma = gpu["merge_assign"][l, g]
+            assert np.array_equal(ma[idx], np.arange(len(idx)))
+            rest = np.setdiff1d(np.arange(wl.seq_len), idx)
+            assert np.all(ma[rest] == -1)
