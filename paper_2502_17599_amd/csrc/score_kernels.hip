@@ -209,7 +209,7 @@ __global__ void __launch_bounds__(256) stats_combine_kernel(ScoreArgs a) {
 // The workgroup walks over all kv heads and, inside, the query heads of the group, so the
 // head-averaged cross-modal probabilities of its W x 128 patch accumulate in registers (same
 // accumulator layout for every head) and the entropy terms p log p can be taken once at the end.
-template <typename T, int D, int RB>
+template <typename T, int D, int RB, bool KSTAGE>
 __global__ void __launch_bounds__(256) score_accum_kernel(ScoreArgs a) {
   using TL = Tile<T, D>;
   extern __shared__ __align__(16) char smem[];
@@ -241,13 +241,15 @@ __global__ void __launch_bounds__(256) score_accum_kernel(ScoreArgs a) {
     for (int r = 0; r < 16; ++r) pbar[rb][r] = 0.f;
 
   // Heads are visited in order h = 0 .. Hq-1 (kv head g = h / G).  The tiles of head h+1 are fetched
-  // into registers while head h is processed out of LDS.
-  TileStage<T, D, kScoreTile> kstage;
+  // into registers while head h is processed out of LDS.  With grouped heads (KSTAGE false) the key
+  // tile changes only every G heads: it is then loaded on the spot, which keeps 32 registers free
+  // (two waves per SIMD instead of one) at the price of one exposed load per group.
+  TileStage<T, D, KSTAGE ? kScoreTile : 1> kstage;
   TileStage<T, D, RB * 32> qstage;
   float4 sreg = make_float4(0.f, 0.f, 0.f, 0.f);
   const char* ktile_src = a.k + ((size_t)l * a.Hkv * a.T + j0) * TL::kRowBytes;
   const size_t khead_stride = (size_t)a.T * TL::kRowBytes;
-  kstage.fetch(ktile_src, rows_valid, tid, 256);
+  if (KSTAGE) kstage.fetch(ktile_src, rows_valid, tid, 256);
   qstage.fetch(a.q + (size_t)(l * a.Hq) * a.W * TL::kRowBytes, a.W, tid, 256);
   if (tid < Wp) sreg = a.stats[(size_t)(l * a.Hq) * a.Wp + tid];
 
@@ -256,7 +258,15 @@ __global__ void __launch_bounds__(256) score_accum_kernel(ScoreArgs a) {
   for (int h = 0; h < a.Hq; ++h) {
     const int g = h / a.G, hg = h - g * a.G;
     __syncthreads();  // the previous head's tiles are no longer read
-    if (hg == 0) kstage.commit(ktile, tid, 256);
+    if (hg == 0) {
+      if (KSTAGE) {
+        kstage.commit(ktile, tid, 256);
+      } else {
+        TileStage<T, D, kScoreTile> now;
+        now.fetch(ktile_src + (size_t)g * khead_stride, rows_valid, tid, 256);
+        now.commit(ktile, tid, 256);
+      }
+    }
     qstage.commit(qtile, tid, 256);
     if (tid < Wp) {
       st_m[tid] = sreg.x;
@@ -267,7 +277,7 @@ __global__ void __launch_bounds__(256) score_accum_kernel(ScoreArgs a) {
     __syncthreads();
     if (h + 1 < a.Hq) {
       const int hn = h + 1;
-      if (hn % a.G == 0) kstage.fetch(ktile_src + (size_t)(hn / a.G) * khead_stride, rows_valid, tid, 256);
+      if (KSTAGE && hn % a.G == 0) kstage.fetch(ktile_src + (size_t)(hn / a.G) * khead_stride, rows_valid, tid, 256);
       qstage.fetch(a.q + (size_t)(l * a.Hq + hn) * a.W * TL::kRowBytes, a.W, tid, 256);
       if (tid < Wp) sreg = a.stats[(size_t)(l * a.Hq + hn) * a.Wp + tid];
     }
@@ -387,10 +397,10 @@ hipError_t launch_stats_combine(const Plan& p, const Buffers& b, hipStream_t s) 
   return hipGetLastError();
 }
 
-template <typename T, int D, int RB>
-static hipError_t launch_accum_t(const Plan& p, const ScoreArgs& a, hipStream_t s) {
+template <typename T, int D, int RB, bool KSTAGE>
+static hipError_t launch_accum_k(const Plan& p, const ScoreArgs& a, hipStream_t s) {
   const size_t lds = (size_t)(kScoreTile + RB * 32) * Tile<T, D>::kStride + 4 * RB * 32 * sizeof(float) + 64;
-  auto kern = score_accum_kernel<T, D, RB>;
+  auto kern = score_accum_kernel<T, D, RB, KSTAGE>;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -398,6 +408,11 @@ static hipError_t launch_accum_t(const Plan& p, const ScoreArgs& a, hipStream_t 
   }
   hipLaunchKernelGGL(kern, dim3(p.NT, p.L), dim3(256), lds, s, a);
   return hipGetLastError();
+}
+
+template <typename T, int D, int RB>
+static hipError_t launch_accum_t(const Plan& p, const ScoreArgs& a, hipStream_t s) {
+  return p.G == 1 ? launch_accum_k<T, D, RB, true>(p, a, s) : launch_accum_k<T, D, RB, false>(p, a, s);
 }
 
 template <typename T, int D>
