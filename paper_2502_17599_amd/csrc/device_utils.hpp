@@ -121,13 +121,13 @@ __device__ __forceinline__ void tile_load_contiguous(char* lds, const char* gsrc
 
 // A tile of ROWS consecutive rows, cut in 16-byte pieces that are dealt round-robin to the threads of
 // the workgroup and held in registers between the global loads (all issued back to back, so they are
-// in flight together) and the stores into the padded LDS tile.  PIECES is sized for 256 threads;
+// in flight together) and the stores into the padded LDS tile.  PIECES is sized for NTHR threads;
 // larger workgroups leave the upper pieces unused.
-template <typename T, int D, int ROWS>
+template <typename T, int D, int ROWS, int NTHR = 256>
 struct TileStage {
   static constexpr int CPR = Tile<T, D>::kChunksPerRow;
   static constexpr int TOTAL = ROWS * CPR;
-  static constexpr int PIECES = (TOTAL + 255) / 256;
+  static constexpr int PIECES = (TOTAL + NTHR - 1) / NTHR;
   uint4 r[PIECES];
 
   __device__ __forceinline__ void fetch(const char* gsrc, int rows_valid, int tid, int n_threads) {

@@ -39,8 +39,7 @@ meda_status make_plan(const meda_params* p, Plan* out) {
   pl.Wp = pl.RB * 32;
   const int combos = pl.G * pl.RB;
   if (combos > 32) return MEDA_ERR_UNSUPPORTED;
-  pl.NQ = 1;
-  while (pl.NQ < 4 && (combos + pl.NQ - 1) / pl.NQ > 4) pl.NQ *= 2;
+  pl.NQ = combos <= 4 ? 1 : (combos <= 16 ? 2 : 4);  // (head, row block) pairs a wave keeps in registers
   pl.NCG = (combos + pl.NQ - 1) / pl.NQ;
   pl.CS = (pl.NCG <= 4) ? 4 / pl.NCG : 1;
   const int tiles = (pl.T + kScoreTile - 1) / kScoreTile;

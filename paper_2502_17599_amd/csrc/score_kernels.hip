@@ -36,15 +36,16 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // every tile of its chunk.  The product is taken with the keys as operand A and the queries as
 // operand B, so a lane owns one query row and 16 keys per block: the running (max, Z_vision, Z_text)
 // of the row live in three registers per fragment and need no cross-lane traffic until the end.
-template <typename T, int D, int NQ>
-__global__ void __launch_bounds__(512) score_stats_kernel(ScoreArgs a) {
+template <typename T, int D, int NQ, int NW>
+__global__ void __launch_bounds__(NW * 64, 2) score_stats_kernel(ScoreArgs a) {
   using TL = Tile<T, D>;
   extern __shared__ __align__(16) char smem[];
   char* ktile = smem;
   uint8_t* lmask = reinterpret_cast<uint8_t*>(smem + kScoreTile * TL::kStride);
 
   const int ch = blockIdx.x, g = blockIdx.y, l = blockIdx.z;
-  const int tid = threadIdx.x, nthr = blockDim.x;
+  constexpr int nthr = NW * 64;
+  const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63, n = lane & 31, kg = lane >> 5;
   const int cgi = wave % a.NCG, cs = wave / a.NCG;
   const bool active = cs < a.CS;  // the workgroup is padded to 4 or 8 waves; spare waves only move data
@@ -78,7 +79,7 @@ __global__ void __launch_bounds__(512) score_stats_kernel(ScoreArgs a) {
   const char* kbase = a.k + (size_t)(l * a.Hkv + g) * a.T * TL::kRowBytes;
   float* invn_out = a.inv_norm + (size_t)(l * a.Hkv + g) * a.T;
 
-  TileStage<T, D, kScoreTile> stage;
+  TileStage<T, D, kScoreTile, nthr> stage;
   uint8_t mreg = 0;
   if (jbeg < jend) {
     stage.fetch(kbase + (size_t)jbeg * TL::kRowBytes, min(kScoreTile, a.T - jbeg), tid, nthr);
@@ -361,18 +362,23 @@ static ScoreArgs make_args(const Plan& p, const Buffers& b) {
   return a;
 }
 
-template <typename T, int D, int NQ>
-static hipError_t launch_stats_t(const Plan& p, const ScoreArgs& a, hipStream_t s) {
+template <typename T, int D, int NQ, int NW>
+static hipError_t launch_stats_w(const Plan& p, const ScoreArgs& a, hipStream_t s) {
   const size_t lds = (size_t)kScoreTile * Tile<T, D>::kStride + kScoreTile;
-  auto kern = score_stats_kernel<T, D, NQ>;
+  auto kern = score_stats_kernel<T, D, NQ, NW>;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  dim3 grid(p.NCH, p.Hkv, p.L), block((p.NCG * p.CS <= 4 ? 4 : 8) * 64);
+  dim3 grid(p.NCH, p.Hkv, p.L), block(NW * 64);
   hipLaunchKernelGGL(kern, grid, block, lds, s, a);
   return hipGetLastError();
+}
+
+template <typename T, int D, int NQ>
+static hipError_t launch_stats_t(const Plan& p, const ScoreArgs& a, hipStream_t s) {
+  return p.NCG * p.CS <= 4 ? launch_stats_w<T, D, NQ, 4>(p, a, s) : launch_stats_w<T, D, NQ, 8>(p, a, s);
 }
 
 template <typename T, int D>
