@@ -144,16 +144,12 @@ __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 
   const int32_t* less = a.less_idx + lbase;
   const char* kbase = a.k;  // positions are stored as row ids over all layers and heads
 
-  Frag<T, D> lf[2];
+  // first the row ids this wave needs (its own rows; rows past the end repeat the last one and are
+  // never stored), so that all index loads of the prologue are in flight before any row load
   const int r0 = row_base + wave * kSimRowsPerWave;
+  int lrow[2];
 #pragma unroll
-  for (int s = 0; s < 2; ++s) {
-    const int ri = r0 + s * 32 + n;
-    if (ri < n_less)
-      frag_load(lf[s], kbase + (size_t)less[ri] * TL::kRowBytes, kg);
-    else
-      frag_zero(lf[s]);
-  }
+  for (int s = 0; s < 2; ++s) lrow[s] = less[min(r0 + s * 32 + n, n_less - 1)];
   RowBest rb[2];
 #pragma unroll
   for (int s = 0; s < 2; ++s) {
@@ -188,6 +184,9 @@ __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 
   if (tid < kSimSlotTile) cinv[buf][tid] = piv;
 
   MEDA_SIM_LOAD_IDX(0)
+  Frag<T, D> lf[2];
+#pragma unroll
+  for (int s = 0; s < 2; ++s) frag_load(lf[s], kbase + (size_t)lrow[s] * TL::kRowBytes, kg);
   MEDA_SIM_ISSUE(0)
   if (ntiles > 1) { MEDA_SIM_LOAD_IDX(1) }
   MEDA_SIM_COMMIT(0)
