@@ -129,10 +129,17 @@ __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 
   __shared__ __align__(16) char ctile[2][kSimSlotTile * TL::kStride];
   __shared__ __align__(16) float cinv[2][kSimSlotTile];
 
-  const int g = blockIdx.y, l = blockIdx.z;
+  // Workgroups are dealt round-robin to the 8 XCDs in launch order.  The launch index is remapped so
+  // that all row blocks of one (layer, head) run on the same XCD (they stream the same conserved keys
+  // and then share one L2), while consecutive (layer, head) pairs go to different XCDs.
+  const unsigned nrb = (a.T + kSimRows - 1) / kSimRows;
+  const unsigned xcd = blockIdx.x & 7u, seq = blockIdx.x >> 3;
+  const unsigned pair = xcd + 8u * (seq / nrb);
+  if (pair >= (unsigned)(a.L * a.Hkv)) return;
+  const int l = pair / a.Hkv, g = pair % a.Hkv;
   const int S = a.alloc[4 * l];
   const int n_less = a.T - S;
-  const int row_base = blockIdx.x * kSimRows;
+  const int row_base = (seq % nrb) * kSimRows;
   if (row_base >= n_less) return;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, kg = lane >> 5;
@@ -587,7 +594,8 @@ static MergeArgs make_args(const Plan& p, const Buffers& b) {
 
 template <typename T, int D>
 static hipError_t launch_sim_t(const Plan& p, const MergeArgs& a, hipStream_t s) {
-  dim3 grid((p.T + kSimRows - 1) / kSimRows, p.Hkv, p.L);
+  const unsigned nrb = (p.T + kSimRows - 1) / kSimRows, pairs = (unsigned)(p.L * p.Hkv);
+  dim3 grid(8u * nrb * ((pairs + 7u) / 8u));
   hipLaunchKernelGGL((similarity_argmax_kernel<T, D>), grid, dim3(kSimWaves * 64), 0, s, a);
   return hipGetLastError();
 }
