@@ -133,3 +133,14 @@ def test_flag_no_merge_copies_the_conserved_rows():
             assert np.array_equal(ma[idx], np.arange(len(idx)))
             rest = np.setdiff1d(np.arange(wl.seq_len), idx)
             assert np.all(ma[rest] == -1)
+
+
+def test_large_window_and_large_groups():
+    # window of 128 rows (four 32-row blocks) with 8 query heads per kv head, and a 96-row window with
+    # vision rows: the largest (head, row block) counts the scoring kernels are built for
+    layout = (("t", 30, -1), ("v", 500, 0), ("t", 100, -1), ("v", 300, 1), ("t", 94, -1))
+    _case(variant(TINY, name="w128_g8", n_layers=2, n_q_heads=8, n_kv_heads=1, head_dim=128, dtype="bf16",
+                  layout=layout, window=128, total_budget=2 * 300, seed=8))
+    layout = (("t", 30, -1), ("v", 500, 0), ("t", 100, -1), ("v", 340, 1), ("t", 54, -1))
+    _case(variant(TINY, name="w96_g4_f32", n_layers=2, n_q_heads=8, n_kv_heads=2, head_dim=64, dtype="f32",
+                  layout=layout, window=96, total_budget=2 * 260, seed=9))
