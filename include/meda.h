@@ -107,8 +107,10 @@ meda_status meda_workspace_region(const meda_params* params, int region, size_t*
 
 /*
  * Per-phase GPU timing.  While enabled, meda_compress records HIP events on its stream around
- * every kernel; meda_profile_read waits for the recorded calls and returns, per phase, the
+ * its kernels; meda_profile_read waits for the recorded calls and returns, per phase, the
  * summed kernel time in milliseconds and the number of calls since the last reset.
+ * meda_profile_enable(0) switches it off, (1) brackets every kernel, (2 + p) brackets only the
+ * kernel of phase p (two events per call instead of nine; the other phases read 0).
  */
 #define MEDA_N_PHASES 8
 /* phases: 0 row statistics + key norms, 1 statistics combine, 2 column scores + entropy,

@@ -103,8 +103,10 @@ def meda_workspace_region(params: MedaParams, region) -> tuple:
     return off.value, size.value
 
 
-def meda_profile_enable(enable: bool) -> None:
-    _check(load_library().meda_profile_enable(1 if enable else 0))
+def meda_profile_enable(enable, phase: Optional[int] = None) -> None:
+    """Off (False), every kernel (True), or only the kernel of ``phase`` (True with a phase index)."""
+    mode = 0 if not enable else (1 if phase is None else 2 + int(phase))
+    _check(load_library().meda_profile_enable(mode))
 
 
 def meda_profile_read(reset: bool = True):

@@ -82,9 +82,11 @@ meda_status make_plan(const meda_params* p, Plan* out) {
 // ------------------------------------------------------------------------------------- profiling
 struct CallEvents {
   hipEvent_t ev[MEDA_N_PHASES + 1];
+  int only;  // -1: every phase was bracketed; p: only phase p (events p and p+1)
 };
 static std::mutex g_mu;
 static bool g_profile = false;
+static int g_only = -1;
 static std::vector<CallEvents> g_pending, g_pool;
 static double g_ms[MEDA_N_PHASES] = {0};
 static int g_calls = 0;
@@ -96,10 +98,11 @@ static bool acquire_events(CallEvents* ce) {
   if (!g_pool.empty()) {
     *ce = g_pool.back();
     g_pool.pop_back();
-    return true;
+  } else {
+    for (int i = 0; i <= MEDA_N_PHASES; ++i)
+      if (hipEventCreate(&ce->ev[i]) != hipSuccess) return false;
   }
-  for (int i = 0; i <= MEDA_N_PHASES; ++i)
-    if (hipEventCreate(&ce->ev[i]) != hipSuccess) return false;
+  ce->only = g_only;
   return true;
 }
 
@@ -158,11 +161,12 @@ meda_status meda_compress(const meda_params* params, const void* q_win, const vo
                                           launch_segment_sort, launch_merge_write};
   const bool no_merge = (pl.flags & MEDA_FLAG_NO_MERGE) || pl.B == (int64_t)pl.L * pl.T;
   hipError_t err = hipSuccess;
-  if (prof) err = hipEventRecord(ce.ev[0], s);
+  if (prof && ce.only <= 0) err = hipEventRecord(ce.ev[0], s);
   for (int i = 0; i < MEDA_N_PHASES && err == hipSuccess; ++i) {
     const bool skip = no_merge && (i == 5 || i == 6);
     if (!skip) err = phases[i](pl, b, s);
-    if (prof && err == hipSuccess) err = hipEventRecord(ce.ev[i + 1], s);
+    const bool rec = prof && (ce.only < 0 || i == ce.only || i + 1 == ce.only);
+    if (rec && err == hipSuccess) err = hipEventRecord(ce.ev[i + 1], s);
   }
   if (prof) {
     std::lock_guard<std::mutex> lk(g_mu);
@@ -172,8 +176,10 @@ meda_status meda_compress(const meda_params* params, const void* q_win, const vo
 }
 
 meda_status meda_profile_enable(int enable) {
+  if (enable < 0 || enable > 1 + MEDA_N_PHASES) return MEDA_ERR_INVALID_ARG;
   std::lock_guard<std::mutex> lk(g_mu);
   g_profile = enable != 0;
+  g_only = enable >= 2 ? enable - 2 : -1;
   return MEDA_OK;
 }
 
@@ -182,8 +188,10 @@ meda_status meda_profile_read(double* phase_ms, int32_t* n_calls, int reset) {
   std::lock_guard<std::mutex> lk(g_mu);
   meda_status st = MEDA_OK;
   for (CallEvents& ce : g_pending) {
-    if (hipEventSynchronize(ce.ev[MEDA_N_PHASES]) != hipSuccess) { st = MEDA_ERR_HIP; continue; }
+    const int last = ce.only < 0 ? MEDA_N_PHASES : ce.only + 1;
+    if (hipEventSynchronize(ce.ev[last]) != hipSuccess) { st = MEDA_ERR_HIP; continue; }
     for (int i = 0; i < MEDA_N_PHASES; ++i) {
+      if (ce.only >= 0 && i != ce.only) continue;
       float ms = 0.f;
       if (hipEventElapsedTime(&ms, ce.ev[i], ce.ev[i + 1]) == hipSuccess) g_ms[i] += ms; else st = MEDA_ERR_HIP;
     }

@@ -98,3 +98,12 @@ def test_binding_refuses_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(L, "_PKG_DIR", str(tmp_path))
     with pytest.raises(pkg.MedaError):
         L.load_library()
+
+
+def test_profile_mode_range(lib):
+    # 0 off, 1 every phase, 2 + p only phase p; nothing is launched, nothing was recorded
+    for mode in (1, 2, 1 + pkg.N_PHASES, 0):
+        assert lib.meda_profile_enable(mode) == 0
+    assert lib.meda_profile_enable(-1) == 1 and lib.meda_profile_enable(2 + pkg.N_PHASES) == 1
+    ms, calls = pkg.meda_profile_read(reset=True)
+    assert calls == 0 and all(m == 0.0 for m in ms)

@@ -144,3 +144,25 @@ def test_large_window_and_large_groups():
     layout = (("t", 30, -1), ("v", 500, 0), ("t", 100, -1), ("v", 340, 1), ("t", 54, -1))
     _case(variant(TINY, name="w96_g4_f32", n_layers=2, n_q_heads=8, n_kv_heads=2, head_dim=64, dtype="f32",
                   layout=layout, window=96, total_budget=2 * 260, seed=9))
+
+
+def test_phase_timers_all_and_single():
+    import paper_2502_17599_amd as pkg
+    wl = variant(TINY, name="timers")
+    data = generate(wl)
+    names = [pkg.meda_phase_name(i) for i in range(pkg.N_PHASES)]
+    try:
+        pkg.meda_profile_enable(True)
+        pkg.meda_profile_read(reset=True)
+        _, ref = run_gpu(wl, data)
+        ms, calls = pkg.meda_profile_read(reset=True)
+        assert calls == 1 and all(m > 0.0 for m in ms)
+        p = names.index("similarity")
+        pkg.meda_profile_enable(True, p)
+        _, a = run_gpu(wl, data)
+        _, b = run_gpu(wl, data)
+        ms, calls = pkg.meda_profile_read(reset=True)
+        assert calls == 2 and ms[p] > 0.0 and all(m == 0.0 for i, m in enumerate(ms) if i != p)
+    finally:
+        pkg.meda_profile_enable(False)
+    assert np.array_equal(a["k_out"], ref["k_out"]) and np.array_equal(b["v_out"], ref["v_out"])
