@@ -97,7 +97,9 @@ typedef enum {
   MEDA_REGION_COL_SCORES = 0, /* float [L][Hkv][T]: cumulative attention score A_s (Section 3.3)    */
   MEDA_REGION_INV_NORM = 1,   /* float [L][Hkv][T]: 1/|k| of every key                              */
   MEDA_REGION_ROW_STATS = 2,  /* float [L][Hq][Wp][4], Wp = W rounded up to 32: log2-domain row max,
-                                 1/Z over all visible keys, 1/Z over the row's cross-modal keys, 0   */
+                                 1/Z over all visible keys, then the row's cross-modal 1/Z as the factor
+                                 for vision columns (text rows, else 0) and for text columns (vision
+                                 rows, else 0)                                                        */
   MEDA_REGION_ALLOC = 3,      /* int32 [L][4]: S_l, M_l, N_l, 0                                     */
   MEDA_REGION_LESS_IDX = 4,   /* int32 ragged: layer l, head g at ((l*T - off[l])*Hkv + g*(T-S_l)): the keys
                                  that are not conserved, ascending, as row ids (l*Hkv+g)*T + position */
