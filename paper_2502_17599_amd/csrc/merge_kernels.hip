@@ -27,6 +27,7 @@ struct MergeArgs {
   int L, Hkv, T, flags;
   int merge_members;        // 0: every output row is a plain copy (no merge requested or nothing to merge)
   long long total_slots;    // B * Hkv
+  int n_members;            // keys that are not conserved, all layers and heads: (L * T - B) * Hkv
 };
 
 __device__ __forceinline__ size_t less_base_of(int l, int g, int T, int Hkv, long long off_l, int S) {
@@ -377,11 +378,11 @@ __global__ void __launch_bounds__(kSortMaxThreads, 8) segment_sort_kernel(MergeA
 }
 
 // ------------------------------------------------------------------------------ merge + write
-// One wave per output row (layer, head, slot).  k_j <- (k_j + sum_{i in N_j} k_i) / (|N_j| + 1) and
-// the same for the values (Section 3.3, average merging).  A lane owns one 16-byte piece of a row,
-// so 64 lanes read 1024 bytes = several rows per step; sums are kept in fp64 (exact for the value
-// ranges of a KV cache, hence independent of the summation order) and rounded once to the
-// storage type.
+// A wave produces a run of consecutive output rows (layer, head, slot), one after the other.
+// k_j <- (k_j + sum_{i in N_j} k_i) / (|N_j| + 1) and the same for the values (Section 3.3, average
+// merging).  A lane owns one 16-byte piece of a row, so 64 lanes read 1024 bytes = several rows per
+// load; sums are kept in fp64 (exact for the value ranges of a KV cache, hence independent of the
+// summation order) and rounded once to the storage type.
 // sum / n for a positive integer n given rinv = fl(1/n): one multiply and one exact-remainder
 // correction.  When sum / n is representable the result is exactly that value, so ties of the final
 // rounding to the storage type fall the same way as with a true division.
@@ -468,40 +469,79 @@ struct OutConv<float> {
   }
 };
 
+// Output rows one wave walks; a lane of the wave holds the list range of one of them.
+constexpr int kMergeRowsPerWave = 16;
+
+// Where a wave is in the flat sequence of load steps of its output rows: row r of the wave, element t
+// of that row's list (element 0 is the conserved row itself, the others its members), and the row's
+// conserved row id, first member index and list length.  All fields are uniform over the wave.
+struct MergeCursor {
+  int r, t, sel, beg, cnt;
+};
+
 template <typename T, int D>
 __global__ void __launch_bounds__(256) merge_write_kernel(MergeArgs a) {
   using TL = Tile<T, D>;
   using CV = OutConv<T>;
   constexpr int LPR = TL::kChunksPerRow;  // lanes per row
-  constexpr int MS = 64 / LPR;            // rows per step
+  constexpr int MS = 64 / LPR;            // rows per load
+  constexpr int STEP = 2 * MS;            // rows per step (two loads per lane and tensor)
   constexpr int E = CV::kElems;
+  constexpr int R = kMergeRowsPerWave;
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // output rows are walked from the last layer to the first: the similarity kernel before this one
   // touched the last layers' keys last
-  const long long w = a.total_slots - 1 - ((long long)blockIdx.x * 4 + wave);
-  if (w < 0) return;
-  // everything the wave needs is indexed by its output row w: no layer / head lookup
-  const int row0 = a.sel_idx[w];
-  int m_beg = 0, m_end = 0;
-  if (a.merge_members) {
-    m_beg = a.seg_beg[w];
-    m_end = a.seg_end[w];
+  const long long w_hi = a.total_slots - ((long long)blockIdx.x * 4 + wave) * R;
+  if (w_hi <= 0) return;
+  const long long w_lo = w_hi > R ? w_hi - R : 0;
+  const int n_out = (int)(w_hi - w_lo);
+  // everything a row needs is indexed by its output row w: no layer / head lookup.  Lane i keeps the
+  // entry of row w_lo + i; lanes past the wave's rows keep a list of length 1 that is never loaded.
+  int m_sel = 0, m_beg = 0, m_cnt = 1;
+  if (lane < n_out) {
+    m_sel = a.sel_idx[w_lo + lane];
+    m_beg = a.seg_beg[w_lo + lane];
+    m_cnt = a.seg_end[w_lo + lane] - m_beg + 1;
   }
   const int32_t* members = a.sort_val[0];
-  const int n_rows = m_end - m_beg + 1;  // the conserved row and its members
   const int sub = lane / LPR, cc = lane - sub * LPR;
   const char* kb = a.k + cc * 16;
   const char* vb = a.v + cc * 16;
-  if (n_rows == 1) {  // nothing merges into this row: bit-exact copy
-    if (sub == 0) {
-      *reinterpret_cast<uint4*>(a.k_out + (size_t)w * TL::kRowBytes + cc * 16) =
-          *reinterpret_cast<const uint4*>(kb + (size_t)row0 * TL::kRowBytes);
-      *reinterpret_cast<uint4*>(a.v_out + (size_t)w * TL::kRowBytes + cc * 16) =
-          *reinterpret_cast<const uint4*>(vb + (size_t)row0 * TL::kRowBytes);
+
+  auto read_entry = [&](MergeCursor& c) {
+    c.sel = __builtin_amdgcn_readlane(m_sel, c.r);
+    c.beg = __builtin_amdgcn_readlane(m_beg, c.r);
+    c.cnt = __builtin_amdgcn_readlane(m_cnt, c.r);
+  };
+  auto advance = [&](MergeCursor& c) {
+    c.t += STEP;
+    if (c.t >= c.cnt) {
+      c.r += 1;  // at most two steps past n_out <= 16, so always a lane of the wave
+      c.t = 0;
+      read_entry(c);
     }
-    return;
-  }
+  };
+  // Row ids of the two rows this lane loads in the step at c.  Every load of the loop is issued
+  // unconditionally (the number of loads in flight is then the same on every path, so a wait for
+  // the oldest ones leaves the younger ones in flight): list positions past the end of the row's
+  // list are clamped into the list array, and their lanes load the conserved row again, which the
+  // sum then skips.
+  const int last_member = a.n_members - 1;
+  auto step_ids = [&](const MergeCursor& c, int& i0, int& i1) {
+    const int e0 = c.t + sub, e1 = e0 + MS;
+    const int p0 = min(max(c.beg - 1 + e0, 0), last_member), p1 = min(c.beg - 1 + e1, last_member);
+    const int m0 = members[p0], m1 = members[p1];
+    i0 = (e0 != 0 && e0 < c.cnt) ? m0 : c.sel;
+    i1 = (e1 < c.cnt) ? m1 : c.sel;
+  };
+  auto fetch = [&](int i0, int i1, uint4 (&k)[2], uint4 (&v)[2]) {
+    k[0] = load16_stream(kb + (size_t)i0 * TL::kRowBytes);
+    v[0] = load16_stream(vb + (size_t)i0 * TL::kRowBytes);
+    k[1] = load16_stream(kb + (size_t)i1 * TL::kRowBytes);
+    v[1] = load16_stream(vb + (size_t)i1 * TL::kRowBytes);
+  };
 
   double ak[E], av[E];
 #pragma unroll
@@ -509,59 +549,100 @@ __global__ void __launch_bounds__(256) merge_write_kernel(MergeArgs a) {
     ak[i] = 0.0;
     av[i] = 0.0;
   }
-  // element -1 of the list is the conserved row itself; 64 list entries are fetched per round with
-  // one coalesced load and handed to the lane groups by shuffles, so all row loads of a round can
-  // be in flight together
-  for (int base = m_beg - 1; base < m_end; base += 64) {
-    const int mine_i = base + lane;
-    const int mine = (mine_i < m_beg) ? row0 : ((mine_i < m_end) ? members[mine_i] : -1);
-    const int cnt = min(64, m_end - base);
-    for (int t = 0; t < cnt; t += 2 * MS) {
-      const int e0 = t + sub, e1 = t + MS + sub;
-      const int r0 = __shfl(mine, e0 & 63, kWave), r1 = __shfl(mine, e1 & 63, kWave);
-      const bool ok0 = e0 < cnt, ok1 = e1 < cnt;
-      uint4 k0 = make_uint4(0, 0, 0, 0), v0 = k0, k1 = k0, v1 = k0;
-      if (ok0) {
-        k0 = *reinterpret_cast<const uint4*>(kb + (size_t)r0 * TL::kRowBytes);
-        v0 = *reinterpret_cast<const uint4*>(vb + (size_t)r0 * TL::kRowBytes);
+  // sums the rows of the step at c (already loaded into k, v); finishes the output row on its last step
+  auto consume = [&](const MergeCursor& c, const uint4 (&k)[2], const uint4 (&v)[2]) {
+    const long long w = w_lo + c.r;
+    if (c.cnt == 1) {  // nothing merges into this row: bit-exact copy
+      if (sub == 0) {
+        *reinterpret_cast<uint4*>(a.k_out + (size_t)w * TL::kRowBytes + cc * 16) = k[0];
+        *reinterpret_cast<uint4*>(a.v_out + (size_t)w * TL::kRowBytes + cc * 16) = v[0];
       }
-      if (ok1) {
-        k1 = *reinterpret_cast<const uint4*>(kb + (size_t)r1 * TL::kRowBytes);
-        v1 = *reinterpret_cast<const uint4*>(vb + (size_t)r1 * TL::kRowBytes);
-      }
-      double tk[E], tv[E];
-      CV::unpack(k0, tk);
-      CV::unpack(v0, tv);
+      return;
+    }
 #pragma unroll
-      for (int i = 0; i < E; ++i) {
-        ak[i] += tk[i];
-        av[i] += tv[i];
-      }
-      CV::unpack(k1, tk);
-      CV::unpack(v1, tv);
+    for (int u = 0; u < 2; ++u) {
+      if (c.t + u * MS + sub < c.cnt) {  // lanes past the end of the list hold a row that does not count
+        double tk[E], tv[E];
+        CV::unpack(k[u], tk);
+        CV::unpack(v[u], tv);
 #pragma unroll
-      for (int i = 0; i < E; ++i) {
-        ak[i] += tk[i];
-        av[i] += tv[i];
+        for (int i = 0; i < E; ++i) {
+          ak[i] += tk[i];
+          av[i] += tv[i];
+        }
       }
     }
+    if (c.t + STEP < c.cnt) return;
+    // Last step of the row: reduce over the lane groups that read different rows.  Each exchange
+    // halves the elements a lane is responsible for (the lower group keeps the lower half), so after
+    // log2(MS) steps a lane holds E / MS finished sums starting at element `ebase` of its 16-byte
+    // piece: the divisions and the stores are spread over all 64 lanes.
+    int ebase = 0;
+    if constexpr (MS >= 2) ebase += reduce_scatter_step<E / 2, LPR>(ak, av, (sub & 1) != 0);
+    if constexpr (MS >= 4) ebase += reduce_scatter_step<E / 4, 2 * LPR>(ak, av, (sub & 2) != 0);
+    if constexpr (MS >= 8) ebase += reduce_scatter_step<E / 8, 4 * LPR>(ak, av, (sub & 4) != 0);
+    constexpr int EPL = E / MS;  // finished elements per lane
+    static_assert(EPL >= 1, "a lane must end up with at least one element");
+    const double denom = (double)c.cnt;
+    const double rinv = 1.0 / denom;
+    char* ko = a.k_out + (size_t)w * TL::kRowBytes + cc * 16 + ebase * (int)sizeof(T);
+    char* vo = a.v_out + (size_t)w * TL::kRowBytes + cc * 16 + ebase * (int)sizeof(T);
+    CV::template store<EPL>(ko, ak, denom, rinv);
+    CV::template store<EPL>(vo, av, denom, rinv);
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      ak[i] = 0.0;
+      av[i] = 0.0;
+    }
+  };
+
+  // Three steps are in progress at any time: the rows of step n are summed while the row loads of
+  // step n + 1 and the list loads of step n + 2 are in flight.  The list loads are issued before the
+  // row loads, so waiting for them one round later does not wait for the younger row loads.  The
+  // loop body is written out twice with the two register sets exchanged, so no loaded value is
+  // copied (a copy would have to wait for its load).  Past the wave's last row the cursors point at
+  // lanes that hold (row 0, empty list): those loads are harmless and never consumed.
+  MergeCursor c0{0, 0, 0, 0, 1};
+  read_entry(c0);
+  MergeCursor c1 = c0;
+  advance(c1);
+  MergeCursor c2 = c1;
+  advance(c2);
+  int ida0, ida1, idb0, idb1;
+  uint4 ka[2], va[2], kb2[2], vb2[2];
+  step_ids(c0, ida0, ida1);
+  step_ids(c1, idb0, idb1);
+  fetch(ida0, ida1, kb2, vb2);
+  while (true) {
+    step_ids(c2, ida0, ida1);
+    fetch(idb0, idb1, ka, va);
+    consume(c0, kb2, vb2);
+    c0 = c1;
+    c1 = c2;
+    advance(c2);
+    if (c0.r >= n_out) break;
+    step_ids(c2, idb0, idb1);
+    fetch(ida0, ida1, kb2, vb2);
+    consume(c0, ka, va);
+    c0 = c1;
+    c1 = c2;
+    advance(c2);
+    if (c0.r >= n_out) break;
   }
-  // Reduce over the lane groups that read different rows.  Each exchange halves the elements a lane
-  // is responsible for (the lower group keeps the lower half), so after log2(MS) steps a lane holds
-  // E / MS finished sums starting at element `ebase` of its 16-byte piece: the divisions and the
-  // stores are spread over all 64 lanes.
-  int ebase = 0;
-  if constexpr (MS >= 2) ebase += reduce_scatter_step<E / 2, LPR>(ak, av, (sub & 1) != 0);
-  if constexpr (MS >= 4) ebase += reduce_scatter_step<E / 4, 2 * LPR>(ak, av, (sub & 2) != 0);
-  if constexpr (MS >= 8) ebase += reduce_scatter_step<E / 8, 4 * LPR>(ak, av, (sub & 4) != 0);
-  constexpr int EPL = E / MS;  // finished elements per lane
-  static_assert(EPL >= 1, "a lane must end up with at least one element");
-  const double denom = (double)n_rows;
-  const double rinv = 1.0 / denom;
-  char* ko = a.k_out + (size_t)w * TL::kRowBytes + cc * 16 + ebase * (int)sizeof(T);
-  char* vo = a.v_out + (size_t)w * TL::kRowBytes + cc * 16 + ebase * (int)sizeof(T);
-  CV::template store<EPL>(ko, ak, denom, rinv);
-  CV::template store<EPL>(vo, av, denom, rinv);
+}
+
+// Rows without merging (no member lists exist): output row w is a copy of its conserved row.
+template <typename T, int D>
+__global__ void __launch_bounds__(256) copy_rows_kernel(MergeArgs a) {
+  using TL = Tile<T, D>;
+  constexpr int LPR = TL::kChunksPerRow;
+  const long long piece = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long w = a.total_slots - 1 - piece / LPR;
+  if (w < 0) return;
+  const int cc = (int)(piece % LPR);
+  const size_t src = (size_t)a.sel_idx[w] * TL::kRowBytes + cc * 16, dst = (size_t)w * TL::kRowBytes + cc * 16;
+  *reinterpret_cast<uint4*>(a.k_out + dst) = load16_stream(a.k + src);
+  *reinterpret_cast<uint4*>(a.v_out + dst) = load16_stream(a.v + src);
 }
 
 // ------------------------------------------------------------------------------------------ launch
@@ -589,6 +670,7 @@ static MergeArgs make_args(const Plan& p, const Buffers& b) {
   a.L = p.L; a.Hkv = p.Hkv; a.T = p.T; a.flags = p.flags;
   a.total_slots = (long long)p.B * p.Hkv;
   a.merge_members = !((p.flags & MEDA_FLAG_NO_MERGE) || p.B == (int64_t)p.L * p.T);
+  a.n_members = (int)(((int64_t)p.L * p.T - p.B) * p.Hkv);
   return a;
 }
 
@@ -615,8 +697,13 @@ hipError_t launch_segment_sort(const Plan& p, const Buffers& b, hipStream_t s) {
 
 template <typename T, int D>
 static hipError_t launch_merge_t(const Plan& p, const MergeArgs& a, hipStream_t s) {
-  const long long blocks = (a.total_slots + 3) / 4;
-  hipLaunchKernelGGL((merge_write_kernel<T, D>), dim3((unsigned)blocks), dim3(256), 0, s, a);
+  if (!a.merge_members) {
+    const long long pieces = a.total_slots * Tile<T, D>::kChunksPerRow;
+    hipLaunchKernelGGL((copy_rows_kernel<T, D>), dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, s, a);
+    return hipGetLastError();
+  }
+  const long long waves = (a.total_slots + kMergeRowsPerWave - 1) / kMergeRowsPerWave;
+  hipLaunchKernelGGL((merge_write_kernel<T, D>), dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -82,7 +82,7 @@ __global__ void __launch_bounds__(NW * 64, 2) score_stats_kernel(ScoreArgs a) {
   TileStage<T, D, kScoreTile, nthr> stage;
   uint8_t mreg = 0;
   if (jbeg < jend) {
-    stage.fetch(kbase + (size_t)jbeg * TL::kRowBytes, min(kScoreTile, a.T - jbeg), tid, nthr);
+    stage.template fetch<true>(kbase + (size_t)jbeg * TL::kRowBytes, min(kScoreTile, a.T - jbeg), tid, nthr);
     if (tid < kScoreTile) mreg = (jbeg + tid < a.T) ? a.mask[jbeg + tid] : 0;
   }
   for (int j0 = jbeg; j0 < jend; j0 += kScoreTile) {
@@ -93,7 +93,7 @@ __global__ void __launch_bounds__(NW * 64, 2) score_stats_kernel(ScoreArgs a) {
     __syncthreads();
     if (j0 + kScoreTile < jend) {  // next tile's loads are in flight while this one is processed
       const int jn = j0 + kScoreTile;
-      stage.fetch(kbase + (size_t)jn * TL::kRowBytes, min(kScoreTile, a.T - jn), tid, nthr);
+      stage.template fetch<true>(kbase + (size_t)jn * TL::kRowBytes, min(kScoreTile, a.T - jn), tid, nthr);
       if (tid < kScoreTile) mreg = (jn + tid < a.T) ? a.mask[jn + tid] : 0;
     }
 
@@ -250,7 +250,7 @@ __global__ void __launch_bounds__(256) score_accum_kernel(ScoreArgs a) {
   float4 sreg = make_float4(0.f, 0.f, 0.f, 0.f);
   const char* ktile_src = a.k + ((size_t)l * a.Hkv * a.T + j0) * TL::kRowBytes;
   const size_t khead_stride = (size_t)a.T * TL::kRowBytes;
-  if (KSTAGE) kstage.fetch(ktile_src, rows_valid, tid, 256);
+  if (KSTAGE) kstage.template fetch<true>(ktile_src, rows_valid, tid, 256);
   qstage.fetch(a.q + (size_t)(l * a.Hq) * a.W * TL::kRowBytes, a.W, tid, 256);
   if (tid < Wp) sreg = a.stats[(size_t)(l * a.Hq) * a.Wp + tid];
 
@@ -264,7 +264,7 @@ __global__ void __launch_bounds__(256) score_accum_kernel(ScoreArgs a) {
         kstage.commit(ktile, tid, 256);
       } else {
         TileStage<T, D, kScoreTile> now;
-        now.fetch(ktile_src + (size_t)g * khead_stride, rows_valid, tid, 256);
+        now.template fetch<true>(ktile_src + (size_t)g * khead_stride, rows_valid, tid, 256);
         now.commit(ktile, tid, 256);
       }
     }
@@ -278,7 +278,7 @@ __global__ void __launch_bounds__(256) score_accum_kernel(ScoreArgs a) {
     __syncthreads();
     if (h + 1 < a.Hq) {
       const int hn = h + 1;
-      if (KSTAGE && hn % a.G == 0) kstage.fetch(ktile_src + (size_t)(hn / a.G) * khead_stride, rows_valid, tid, 256);
+      if (KSTAGE && hn % a.G == 0) kstage.template fetch<true>(ktile_src + (size_t)(hn / a.G) * khead_stride, rows_valid, tid, 256);
       qstage.fetch(a.q + (size_t)(l * a.Hq + hn) * a.W * TL::kRowBytes, a.W, tid, 256);
       if (tid < Wp) sreg = a.stats[(size_t)(l * a.Hq + hn) * a.Wp + tid];
     }
