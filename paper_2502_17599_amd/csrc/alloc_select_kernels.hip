@@ -32,20 +32,24 @@ __global__ void __launch_bounds__(256) allocate_kernel(AllocArgs a) {
   const int tid = threadIdx.x, L = a.L;
   const double lo = (double)min(a.W, a.T), hi = (double)a.T, B = (double)a.B;
 
-  if (tid < L) {
-    int n_text = 0, n_vis = 0;
-    for (int i = 0; i < a.W; ++i) {
-      if (a.mask[a.T - a.W + i]) ++n_vis; else ++n_text;
-    }
+  // window rows of each modality (the denominators of the two entropy means)
+  const int n_vis = __syncthreads_count(tid < a.W && a.mask[a.T - a.W + tid] != 0);
+  const int n_text = a.W - n_vis;
+  // per-tile entropy partials of a layer are summed by one wave (lanes stride over the tiles)
+  for (int l = tid >> 6; l < L; l += blockDim.x >> 6) {
+    const double* p = a.ent_part + (size_t)l * a.NT * 2;
     double tv = 0.0, vt = 0.0;
-    const double* p = a.ent_part + (size_t)tid * a.NT * 2;
-    for (int t = 0; t < a.NT; ++t) {
+    for (int t = tid & 63; t < a.NT; t += 64) {
       tv += p[2 * t];
       vt += p[2 * t + 1];
     }
-    const double e = (n_text ? tv / n_text : 0.0) + (n_vis ? vt / n_vis : 0.0);
-    E[tid] = e;
-    if (a.entropy) a.entropy[tid] = e;
+    tv = wave_sum(tv);
+    vt = wave_sum(vt);
+    if ((tid & 63) == 0) {
+      const double e = (n_text ? tv / n_text : 0.0) + (n_vis ? vt / n_vis : 0.0);
+      E[l] = e;
+      if (a.entropy) a.entropy[l] = e;
+    }
   }
   __syncthreads();
 
@@ -117,21 +121,24 @@ __global__ void __launch_bounds__(256) allocate_kernel(AllocArgs a) {
         const int lyr = order[r];
         if (S[lyr] > min(a.W, a.T)) { --S[lyr]; ++rest; }
       }
+  }
+  __syncthreads();
+  if (tid < L) {
+    const int s = S[tid];
+    const int m = max(min(a.W, s), (int)(((long long)s * a.num) / a.den));
     long long o = 0;
-    for (int j = 0; j < L; ++j) {
-      const int s = S[j];
-      const int m = max(min(a.W, s), (int)(((long long)s * a.num) / a.den));
-      a.alloc[4 * j + 0] = s;
-      a.alloc[4 * j + 1] = m;
-      a.alloc[4 * j + 2] = s - m;
-      a.alloc[4 * j + 3] = 0;
-      a.off[j] = o;
-      a.layer_len[j] = s;
-      a.layer_off[j] = o;
-      o += s;
+    for (int j = 0; j < tid; ++j) o += S[j];
+    a.alloc[4 * tid + 0] = s;
+    a.alloc[4 * tid + 1] = m;
+    a.alloc[4 * tid + 2] = s - m;
+    a.alloc[4 * tid + 3] = 0;
+    a.off[tid] = o;
+    a.layer_len[tid] = s;
+    a.layer_off[tid] = o;
+    if (tid == L - 1) {
+      a.off[L] = o + s;
+      a.layer_off[L] = o + s;
     }
-    a.off[L] = o;
-    a.layer_off[L] = o;
   }
 }
 

@@ -551,6 +551,12 @@ __global__ void __launch_bounds__(256) merge_write_kernel(MergeArgs a) {
   }
   // sums the rows of the step at c (already loaded into k, v); finishes the output row on its last step
   auto consume = [&](const MergeCursor& c, const uint4 (&k)[2], const uint4 (&v)[2]) {
+    // One unconditional use of everything the step loaded: the wait for these loads then sits here on
+    // every path, instead of inside the branches below (which would leave them formally in flight on
+    // the other paths and force wider waits later).
+    asm volatile("" ::"v"(k[0].x), "v"(k[0].y), "v"(k[0].z), "v"(k[0].w), "v"(k[1].x), "v"(k[1].y), "v"(k[1].z),
+                 "v"(k[1].w), "v"(v[0].x), "v"(v[0].y), "v"(v[0].z), "v"(v[0].w), "v"(v[1].x), "v"(v[1].y),
+                 "v"(v[1].z), "v"(v[1].w));
     const long long w = w_lo + c.r;
     if (c.cnt == 1) {  // nothing merges into this row: bit-exact copy
       if (sub == 0) {
@@ -613,21 +619,22 @@ __global__ void __launch_bounds__(256) merge_write_kernel(MergeArgs a) {
   step_ids(c0, ida0, ida1);
   step_ids(c1, idb0, idb1);
   fetch(ida0, ida1, kb2, vb2);
+  // one step: true when the wave's last row is done
+  auto round = [&](int& new0, int& new1, int old0, int old1, uint4 (&nk)[2], uint4 (&nv)[2], const uint4 (&ok)[2],
+                   const uint4 (&ov)[2]) {
+    step_ids(c2, new0, new1);
+    fetch(old0, old1, nk, nv);
+    consume(c0, ok, ov);
+    c0 = c1;
+    c1 = c2;
+    advance(c2);
+    return c0.r >= n_out;
+  };
   while (true) {
-    step_ids(c2, ida0, ida1);
-    fetch(idb0, idb1, ka, va);
-    consume(c0, kb2, vb2);
-    c0 = c1;
-    c1 = c2;
-    advance(c2);
-    if (c0.r >= n_out) break;
-    step_ids(c2, idb0, idb1);
-    fetch(ida0, ida1, kb2, vb2);
-    consume(c0, ka, va);
-    c0 = c1;
-    c1 = c2;
-    advance(c2);
-    if (c0.r >= n_out) break;
+    if (round(ida0, ida1, idb0, idb1, ka, va, kb2, vb2)) break;
+    if (round(idb0, idb1, ida0, ida1, kb2, vb2, ka, va)) break;
+    if (round(ida0, ida1, idb0, idb1, ka, va, kb2, vb2)) break;
+    if (round(idb0, idb1, ida0, ida1, kb2, vb2, ka, va)) break;
   }
 }
 

@@ -37,7 +37,7 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // operand B, so a lane owns one query row and 16 keys per block: the running (max, Z_vision, Z_text)
 // of the row live in three registers per fragment and need no cross-lane traffic until the end.
 template <typename T, int D, int NQ, int NW>
-__global__ void __launch_bounds__(NW * 64, 2) score_stats_kernel(ScoreArgs a) {
+__global__ void __launch_bounds__(NW * 64, (NQ == 1 && NW == 4 && sizeof(T) == 2) ? 3 : 2) score_stats_kernel(ScoreArgs a) {
   using TL = Tile<T, D>;
   extern __shared__ __align__(16) char smem[];
   char* ktile = smem;
@@ -97,6 +97,7 @@ __global__ void __launch_bounds__(NW * 64, 2) score_stats_kernel(ScoreArgs a) {
       if (tid < kScoreTile) mreg = (jn + tid < a.T) ? a.mask[jn + tid] : 0;
     }
 
+#ifndef MEDA_EXP_A_NOCOMPUTE
     // 1/|k| of the tile's keys: two threads per row
     for (int row = tid >> 1; row < kScoreTile; row += nthr >> 1) {
       const uint4* p = reinterpret_cast<const uint4*>(ktile + row * TL::kStride + (tid & 1) * TL::kHalfBytes);
@@ -159,6 +160,7 @@ __global__ void __launch_bounds__(NW * 64, 2) score_stats_kernel(ScoreArgs a) {
         }
       }
     }
+#endif
   }
 
   // the two lane groups hold disjoint keys of the same query row: merge them, then store the partial
