@@ -171,13 +171,13 @@ template <typename T>
 __device__ __forceinline__ float chunk_sumsq(const uint4& v);
 template <>
 __device__ __forceinline__ float chunk_sumsq<bf16_t>(const uint4& v) {
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
   float s = 0.f;
   const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const float lo = __uint_as_float(w[i] << 16), hi = __uint_as_float(w[i] & 0xffff0000u);
-    s = fmaf(lo, lo, s);
-    s = fmaf(hi, hi, s);
+  for (int i = 0; i < 4; ++i) {  // one packed dot product per pair of elements
+    const bf16x2_t p = __builtin_bit_cast(bf16x2_t, w[i]);
+    s = __builtin_amdgcn_fdot2_f32_bf16(p, p, s, false);
   }
   return s;
 }

@@ -213,7 +213,7 @@ __global__ void __launch_bounds__(256) stats_combine_kernel(ScoreArgs a) {
 // head-averaged cross-modal probabilities of its W x 128 patch accumulate in registers (same
 // accumulator layout for every head) and the entropy terms p log p can be taken once at the end.
 template <typename T, int D, int RB, bool KSTAGE>
-__global__ void __launch_bounds__(256) score_accum_kernel(ScoreArgs a) {
+__global__ void __launch_bounds__(256, (RB == 1 && sizeof(T) == 2 && !KSTAGE) ? 3 : 1) score_accum_kernel(ScoreArgs a) {
   using TL = Tile<T, D>;
   extern __shared__ __align__(16) char smem[];
   char* ktile = smem;
@@ -420,7 +420,11 @@ static hipError_t launch_accum_k(const Plan& p, const ScoreArgs& a, hipStream_t 
 
 template <typename T, int D, int RB>
 static hipError_t launch_accum_t(const Plan& p, const ScoreArgs& a, hipStream_t s) {
-  return p.G == 1 ? launch_accum_k<T, D, RB, true>(p, a, s) : launch_accum_k<T, D, RB, false>(p, a, s);
+  // Staging the next head's key tile through registers pays when every head brings a new key tile
+  // (G == 1), except for the smallest shape, where the registers buy a third workgroup per CU instead.
+  constexpr bool kThreeGroups = RB == 1 && sizeof(T) == 2;
+  if (p.G == 1 && !kThreeGroups) return launch_accum_k<T, D, RB, true>(p, a, s);
+  return launch_accum_k<T, D, RB, false>(p, a, s);
 }
 
 template <typename T, int D>
