@@ -131,7 +131,11 @@ __global__ void __launch_bounds__(256) allocate_kernel(AllocArgs a) {
     a.alloc[4 * tid + 0] = s;
     a.alloc[4 * tid + 1] = m;
     a.alloc[4 * tid + 2] = s - m;
-    a.alloc[4 * tid + 3] = 0;
+    // layers ranked by decreasing budget (ties: lower layer first), for kernels that launch the
+    // longest workgroups first
+    int rank = 0;
+    for (int j = 0; j < L; ++j) rank += (S[j] > s || (S[j] == s && j < tid)) ? 1 : 0;
+    a.alloc[4 * rank + 3] = tid;
     a.off[tid] = o;
     a.layer_len[tid] = s;
     a.layer_off[tid] = o;

@@ -27,6 +27,7 @@ struct MergeArgs {
   int L, Hkv, T, flags;
   int merge_members;        // 0: every output row is a plain copy (no merge requested or nothing to merge)
   long long total_slots;    // B * Hkv
+  int use_resident;         // layers whose conserved set fits into LDS go to the resident-set kernel
   int n_members;            // keys that are not conserved, all layers and heads: (L * T - B) * Hkv
 };
 
@@ -41,6 +42,21 @@ __device__ __forceinline__ int sort_passes(int S) {
 }
 
 // ------------------------------------------------------------------------ similarity + argmax
+// Layers whose conserved set fits into LDS go to the resident-set kernel (one workgroup of 8 waves per
+// (layer, head) part, all 160 KB of LDS), the others to the tiled kernel; both are launched and every
+// workgroup looks up its layer's budget.
+constexpr int kResWaves = 8;
+constexpr int kResThreads = kResWaves * 64;
+constexpr int kResLdsBytes = 160 * 1024;
+constexpr int kResSplit = 1;
+
+// conserved keys (a multiple of 32) that fit: one padded row and one 1/|k| each
+template <typename T, int D>
+constexpr int resident_capacity() {
+  // rows above 256 bytes would need more registers per wave than eight waves per CU leave
+  return Tile<T, D>::kRowBytes > 256 ? 0 : kResLdsBytes / (Tile<T, D>::kStride + 4) / 32 * 32;
+}
+
 // grid (ceil(T / 256), Hkv, L); 4 waves x 64 less-important rows.  u_ij = (k_i . k_j)/(|k_i| |k_j|):
 // the raw keys are multiplied (bf16 products are exact in the fp32 accumulator), the factor 1/|k_j|
 // of the conserved key is applied to the accumulator, and the positive factor 1/|k_i| of the row is
@@ -137,8 +153,9 @@ __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 
   const unsigned xcd = blockIdx.x & 7u, seq = blockIdx.x >> 3;
   const unsigned pair = xcd + 8u * (seq / nrb);
   if (pair >= (unsigned)(a.L * a.Hkv)) return;
-  const int l = pair / a.Hkv, g = pair % a.Hkv;
+  const int l = a.alloc[4 * (pair / a.Hkv) + 3], g = pair % a.Hkv;  // layers by decreasing budget
   const int S = a.alloc[4 * l];
+  if (a.use_resident && S <= resident_capacity<T, D>()) return;  // the resident-set kernel below takes this layer
   const int n_less = a.T - S;
   const int row_base = (seq % nrb) * kSimRows;
   if (row_base >= n_less) return;
@@ -223,6 +240,140 @@ __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 
     if (kg == 0 && ri < n_less) {
       a.less_slot[lbase + ri] = bi;
       if (a.merge_assign) a.merge_assign[less[ri]] = bi;
+    }
+  }
+}
+
+// Variant for layers whose conserved set fits into LDS: one workgroup keeps ALL conserved keys of its
+// (layer, head) resident and every wave streams chunks of 64 less-important rows through registers.
+// After the prologue there is no barrier: the waves run independently, each MFMA phase of one wave
+// overlaps the argmax phase and the row loads of the others, and the keys are read from HBM once.
+// grid (kResSplit * L * Hkv): part p of a pair takes the chunks p*8 + wave, then steps of 8*kResSplit.
+// Layers above the capacity are left to the tiled kernel above (and skipped there when they fit).
+template <typename T, int D>
+__global__ void __launch_bounds__(kResThreads, 2) similarity_resident_kernel(MergeArgs a) {
+  using TL = Tile<T, D>;
+  constexpr int CPR = TL::kChunksPerRow;
+  extern __shared__ __align__(16) char smem[];
+
+  // workgroups are launched in the order of decreasing budget (longest first: the last ones to start
+  // are the shortest), alloc[4 * rank + 3] is the layer of that rank
+  const int pair = blockIdx.x / kResSplit, part = blockIdx.x % kResSplit;
+  const int l = a.alloc[4 * (pair / a.Hkv) + 3], g = pair % a.Hkv;
+  const int S = a.alloc[4 * l];
+  const int n_less = a.T - S;
+  if (S > resident_capacity<T, D>() || n_less == 0) return;
+  const int n_chunks = (n_less + kSimRowsPerWave - 1) / kSimRowsPerWave;
+  if (part * kResWaves >= n_chunks) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, kg = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const long long off_l = a.off[l];
+  const size_t cbase = (size_t)off_l * a.Hkv + (size_t)g * S;
+  const int32_t* cidx = a.sel_idx + cbase;
+  const float* sinv = a.sel_inv_norm + cbase;
+  const size_t lbase = less_base_of(l, g, a.T, a.Hkv, off_l, S);
+  const int32_t* less = a.less_idx + lbase;
+  const char* kbase = a.k;  // positions are stored as row ids over all layers and heads
+
+  // the wave's first rows are requested before the conserved set, so they arrive during the prologue
+  int c = part * kResWaves + wave;
+  constexpr int kChunkStep = kResWaves * kResSplit;
+  auto chunk_rows = [&](int chunk, int (&rows)[2]) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s) rows[s] = less[min(chunk * kSimRowsPerWave + s * 32 + n, n_less - 1)];
+  };
+  int lrow[2], nrow[2];
+  chunk_rows(c, lrow);
+  chunk_rows(c + kChunkStep, nrow);
+  Frag<T, D> lf[2];
+#pragma unroll
+  for (int s = 0; s < 2; ++s) frag_load(lf[s], kbase + (size_t)lrow[s] * TL::kRowBytes, kg);
+
+  // Prologue: gather the conserved keys into LDS.  The set is padded to a multiple of 32 slots with
+  // copies of the last key (a copy can never win a tie against the original, see sim_tile).
+  const int S_pad = (S + 31) & ~31;
+  char* ckeys = smem;
+  float* cinv = reinterpret_cast<float*>(smem + (size_t)S_pad * TL::kStride);
+  constexpr int kBatch = 6;  // pieces per thread whose loads are in flight together
+  const int n_pieces = S_pad * CPR;
+  for (int p0 = tid; p0 < n_pieces; p0 += kBatch * kResThreads) {
+    int ridx[kBatch];
+    uint4 v[kBatch];
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) {
+      const int p = min(p0 + i * kResThreads, n_pieces - 1);
+      ridx[i] = cidx[min(p / CPR, S - 1)];
+    }
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) {
+      const int p = min(p0 + i * kResThreads, n_pieces - 1);
+      v[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)ridx[i] * TL::kRowBytes + (p % CPR) * 16);
+    }
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) {
+      const int p = p0 + i * kResThreads;
+      if (p < n_pieces) *reinterpret_cast<uint4*>(ckeys + (p / CPR) * TL::kStride + (p % CPR) * 16) = v[i];
+    }
+  }
+  for (int sl = tid; sl < S_pad; sl += kResThreads) cinv[sl] = sinv[min(sl, S - 1)];
+  __syncthreads();
+
+  while (c < n_chunks) {
+    // the rows of the wave's next chunk and the row ids of the one after it are in flight while
+    // this chunk is multiplied (past the last chunk they repeat the last row and are dropped)
+    const int r0 = c * kSimRowsPerWave;
+    Frag<T, D> lfn[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) frag_load(lfn[s], kbase + (size_t)nrow[s] * TL::kRowBytes, kg);
+    int nnrow[2];
+    chunk_rows(c + 2 * kChunkStep, nnrow);
+    RowBest rb[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      rb[s].best = -INFINITY;
+      rb[s].slot0 = 0;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) rb[s].u[r] = -INFINITY;
+    }
+    for (int s0 = 0; s0 < S_pad; s0 += 32) {
+      Frag<T, D> cf;
+      frag_load(cf, ckeys + (s0 + n) * TL::kStride, kg);
+      float iv[16];
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const float4 v = *reinterpret_cast<const float4*>(cinv + s0 + r4 * 8 + kg * 4);
+        iv[r4 * 4 + 0] = v.x;
+        iv[r4 * 4 + 1] = v.y;
+        iv[r4 * 4 + 2] = v.z;
+        iv[r4 * 4 + 3] = v.w;
+      }
+      f32x16_t acc0 = acc_zero(), acc1 = acc_zero();
+      mma<T, D>(acc0, cf, lf[0]);
+      mma<T, D>(acc1, cf, lf[1]);
+      argmax_block(acc0, iv, s0, rb[0]);
+      argmax_block(acc1, iv, s0, rb[1]);
+    }
+    // the two lane groups saw disjoint slots of the same row: keep the better, ties -> lower slot
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const int mine = row_best_slot(rb[s], kg);
+      const float ov = __shfl_xor(rb[s].best, 32, kWave);
+      const int oi = __shfl_xor(mine, 32, kWave);
+      const bool take = ov > rb[s].best || (ov == rb[s].best && oi < mine);
+      const int bi = take ? oi : mine;
+      const int ri = r0 + s * 32 + n;
+      if (kg == 0 && ri < n_less) {
+        a.less_slot[lbase + ri] = bi;
+        if (a.merge_assign) a.merge_assign[lrow[s]] = bi;
+      }
+    }
+    c += kChunkStep;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      lrow[s] = nrow[s];
+      nrow[s] = nnrow[s];
+      lf[s] = lfn[s];
     }
   }
 }
@@ -676,16 +827,26 @@ static MergeArgs make_args(const Plan& p, const Buffers& b) {
   a.merge_assign = b.merge_assign;
   a.L = p.L; a.Hkv = p.Hkv; a.T = p.T; a.flags = p.flags;
   a.total_slots = (long long)p.B * p.Hkv;
+  a.use_resident = 0;
   a.merge_members = !((p.flags & MEDA_FLAG_NO_MERGE) || p.B == (int64_t)p.L * p.T);
   a.n_members = (int)(((int64_t)p.L * p.T - p.B) * p.Hkv);
   return a;
 }
 
 template <typename T, int D>
-static hipError_t launch_sim_t(const Plan& p, const MergeArgs& a, hipStream_t s) {
+static hipError_t launch_sim_t(const Plan& p, MergeArgs a, hipStream_t s) {
   const unsigned nrb = (p.T + kSimRows - 1) / kSimRows, pairs = (unsigned)(p.L * p.Hkv);
+  // one resident-set workgroup occupies a whole CU: only worth it with at least one per CU
+  a.use_resident = (resident_capacity<T, D>() > 0 && pairs >= 256u) ? 1 : 0;
   dim3 grid(8u * nrb * ((pairs + 7u) / 8u));
   hipLaunchKernelGGL((similarity_argmax_kernel<T, D>), grid, dim3(kSimWaves * 64), 0, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (!a.use_resident) return hipSuccess;
+  auto res = similarity_resident_kernel<T, D>;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(res), hipFuncAttributeMaxDynamicSharedMemorySize, kResLdsBytes);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(res, dim3(pairs * kResSplit), dim3(kResThreads), kResLdsBytes, s, a);
   return hipGetLastError();
 }
 
