@@ -97,7 +97,6 @@ __global__ void __launch_bounds__(NW * 64, (NQ == 1 && NW == 4 && sizeof(T) == 2
       if (tid < kScoreTile) mreg = (jn + tid < a.T) ? a.mask[jn + tid] : 0;
     }
 
-#ifndef MEDA_EXP_A_NOCOMPUTE
     // 1/|k| of the tile's keys: two threads per row
     for (int row = tid >> 1; row < kScoreTile; row += nthr >> 1) {
       const uint4* p = reinterpret_cast<const uint4*>(ktile + row * TL::kStride + (tid & 1) * TL::kHalfBytes);
@@ -160,7 +159,6 @@ __global__ void __launch_bounds__(NW * 64, (NQ == 1 && NW == 4 && sizeof(T) == 2
         }
       }
     }
-#endif
   }
 
   // the two lane groups hold disjoint keys of the same query row: merge them, then store the partial
