@@ -20,6 +20,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+# kernels a phase launches (the similarity step is one launch of each of its two kernels: a layer goes to the
+# resident-set kernel when its conserved keys fit into LDS, else to the tiled one)
+PHASE_KERNELS = {"score_stats": ["score_stats_kernel"], "stats_combine": ["stats_combine_kernel"],
+                 "score_accum": ["score_accum_kernel"], "allocate": ["allocate_kernel"], "select": ["select_kernel"],
+                 "similarity": ["similarity_argmax_kernel", "similarity_resident_kernel"],
+                 "segment_sort": ["segment_sort_kernel"], "merge_write": ["merge_write_kernel"]}
 PHASE_BOUND = {"score_stats": "hbm", "score_accum": "hbm", "similarity": "mfma", "merge_write": "hbm",
                "select": "hbm", "segment_sort": "hbm", "stats_combine": "hbm", "allocate": "hbm"}
 
@@ -168,7 +174,7 @@ def main():
             achieved, peak, unit = work[dom] / t_s / 1e12, MFMA_PEAK_TFLOPS[wl.dtype], "TFLOP/s"
         else:
             achieved, peak, unit = work[dom] / t_s / 1e9, HBM_PEAK_GBS, "GB/s"
-        roofline = {"kernel": dom, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+        roofline = {"kernel": dom, "launches": PHASE_KERNELS[dom], "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
                     "frac": achieved / peak, "traffic": measured_traffic(wl.name, dom),
                     "kernel_ms": dom_ms, "launches_timed": n_calls}
 
