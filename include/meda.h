@@ -123,6 +123,42 @@ const char* meda_phase_name(int phase);
 
 const char* meda_status_string(meda_status status);
 
+/*
+ * One decoding step over the compressed cache (Section 3.1, "Decoding with Multimodal KV Cache"):
+ * for every layer and query head, out = Softmax(q K^T * scale) V over the rows the compression pass
+ * kept for that layer (the ragged layout meda_compress writes: layer l holds [Hkv][S_l][d] from row
+ * layer_off[l] * Hkv) followed by the rows appended since then, K = [K, k_t], V = [V, v_t].  Query
+ * head h reads kv head h / (Hq/Hkv).  The order of the rows has no influence on the result.
+ */
+typedef struct {
+  int32_t n_layers;     /* L                                                                        */
+  int32_t n_q_heads;    /* Hq                                                                       */
+  int32_t n_kv_heads;   /* Hkv, Hq % Hkv == 0, Hq / Hkv <= 8                                        */
+  int32_t head_dim;     /* d: 64 or 128                                                             */
+  int32_t n_new;        /* rows appended per layer and kv head since the cache was compressed (>= 0) */
+  int32_t dtype;        /* meda_dtype of q, the caches, the appended rows and out                    */
+  int64_t total_budget; /* B = sum_l S_l (used to size the split of the work; >= L)                  */
+  float softmax_scale;  /* 0 -> 1/sqrt(head_dim)                                                    */
+} meda_decode_params;
+
+/* Bytes of workspace meda_decode_attention needs (multiple of 256); 0 if the parameters are invalid. */
+size_t meda_decode_workspace_bytes(const meda_decode_params* params);
+
+/*
+ * q        [L][Hq][d]                    the query of the new position, one per layer and head
+ * k_cache, v_cache                       ragged compressed cache, B * Hkv rows of d elements
+ * layer_len [L] int32, layer_off [L+1] int64   DEVICE arrays as written by meda_compress
+ * k_new, v_new [L][Hkv][n_new][d]        rows appended since; may be NULL when n_new == 0
+ * out      [L][Hq][d]                    attention output, one rounding to the storage type
+ * workspace                              256-byte aligned, at least meda_decode_workspace_bytes()
+ * All data pointers are device pointers, 16-byte aligned; nothing is allocated; the work is enqueued on
+ * hip_stream.  Errors as for meda_compress (MEDA_ERR_UNSUPPORTED for a group size above 8).
+ */
+meda_status meda_decode_attention(const meda_decode_params* params, const void* q, const void* k_cache,
+                                  const void* v_cache, const int32_t* layer_len, const int64_t* layer_off,
+                                  const void* k_new, const void* v_new, void* out, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -4,12 +4,14 @@ The work is done by libmeda.so (hand-written HIP for gfx950, C ABI declared in i
 this package is the thin Python binding with the same names.  There is no CPU fallback: if the
 library has not been built, every call raises.
 """
-from ._lib import (MedaError, MedaParams, Compressor, CompressedCache, load_library, library_path,
+from ._lib import (MedaError, MedaParams, MedaDecodeParams, Decoder, make_decode_params, meda_decode_attention,
+                   meda_decode_workspace_bytes, Compressor, CompressedCache, load_library, library_path,
                    make_params, meda_compress, meda_workspace_bytes, meda_workspace_region,
                    meda_profile_enable, meda_profile_read, meda_phase_name, meda_status_string,
                    EXPORTED_SYMBOLS, REGIONS, N_PHASES, FLAG_UNIFORM_BUDGET, FLAG_NO_MERGE)
 
-__all__ = ["MedaError", "MedaParams", "Compressor", "CompressedCache", "load_library", "library_path",
+__all__ = ["MedaError", "MedaParams", "MedaDecodeParams", "Decoder", "make_decode_params", "meda_decode_attention",
+           "meda_decode_workspace_bytes", "Compressor", "CompressedCache", "load_library", "library_path",
            "make_params", "meda_compress", "meda_workspace_bytes", "meda_workspace_region",
            "meda_profile_enable", "meda_profile_read", "meda_phase_name", "meda_status_string",
            "EXPORTED_SYMBOLS", "REGIONS", "N_PHASES", "FLAG_UNIFORM_BUDGET", "FLAG_NO_MERGE"]

@@ -12,7 +12,8 @@ _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libmeda.so"
 
 EXPORTED_SYMBOLS = ("meda_workspace_bytes", "meda_compress", "meda_workspace_region",
-                    "meda_profile_enable", "meda_profile_read", "meda_phase_name", "meda_status_string")
+                    "meda_profile_enable", "meda_profile_read", "meda_phase_name", "meda_status_string",
+                    "meda_decode_workspace_bytes", "meda_decode_attention")
 REGIONS = {"col_scores": 0, "inv_norm": 1, "row_stats": 2, "alloc": 3, "less_idx": 4, "less_slot": 5}
 N_PHASES = 8
 FLAG_UNIFORM_BUDGET = 1
@@ -31,6 +32,12 @@ class MedaParams(ctypes.Structure):
                 ("head_dim", ctypes.c_int32), ("seq_len", ctypes.c_int32), ("window", ctypes.c_int32),
                 ("total_budget", ctypes.c_int64), ("recent_num", ctypes.c_int32), ("recent_den", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("flags", ctypes.c_int32)]
+
+
+class MedaDecodeParams(ctypes.Structure):
+    _fields_ = [("n_layers", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("n_new", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("total_budget", ctypes.c_int64), ("softmax_scale", ctypes.c_float)]
 
 
 def library_path() -> str:
@@ -67,6 +74,11 @@ def load_library() -> ctypes.CDLL:
     lib.meda_phase_name.argtypes = [ctypes.c_int]
     lib.meda_status_string.restype = ctypes.c_char_p
     lib.meda_status_string.argtypes = [ctypes.c_int]
+    dp = ctypes.POINTER(MedaDecodeParams)
+    lib.meda_decode_workspace_bytes.restype = ctypes.c_size_t
+    lib.meda_decode_workspace_bytes.argtypes = [dp]
+    lib.meda_decode_attention.restype = ctypes.c_int
+    lib.meda_decode_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     _lib = lib
     return lib
 
@@ -206,3 +218,45 @@ def meda_compress(q_win, k, v, modality, total_budget, recent_num=3, recent_den=
                          softmax_scale, flags)
     comp = Compressor(params, q_win.device, want_merge_assign=want_merge_assign)
     return comp(q_win, k, v, modality, stream)
+
+
+def make_decode_params(n_layers, n_q_heads, n_kv_heads, head_dim, total_budget, dtype, n_new=0,
+                       softmax_scale=0.0) -> MedaDecodeParams:
+    code = _DTYPES.get(dtype, dtype if isinstance(dtype, int) else -1)
+    return MedaDecodeParams(n_layers, n_q_heads, n_kv_heads, head_dim, n_new, code, total_budget, softmax_scale)
+
+
+def meda_decode_workspace_bytes(params: MedaDecodeParams) -> int:
+    return int(load_library().meda_decode_workspace_bytes(ctypes.byref(params)))
+
+
+class Decoder:
+    """Holds the workspace and the output row for meda_decode_attention calls with fixed parameters."""
+
+    def __init__(self, params: MedaDecodeParams, device="cuda:0"):
+        self.params = params
+        self.device = torch.device(device)
+        need = meda_decode_workspace_bytes(params)
+        if need == 0:
+            raise MedaError(1, "invalid or unsupported decode parameters")
+        self.workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
+        dt = torch.bfloat16 if params.dtype == 1 else torch.float32
+        self.out = torch.empty(params.n_layers, params.n_q_heads, params.head_dim, dtype=dt, device=self.device)
+
+    def __call__(self, q, k_cache, v_cache, layer_len, layer_off, k_new=None, v_new=None, stream=None):
+        stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        _check(load_library().meda_decode_attention(
+            ctypes.byref(self.params), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(layer_len), _ptr(layer_off),
+            _ptr(k_new), _ptr(v_new), _ptr(self.out), _ptr(self.workspace), self.workspace.numel(),
+            ctypes.c_void_p(stream.cuda_stream)))
+        return self.out
+
+
+def meda_decode_attention(q, cache: "CompressedCache", k_new=None, v_new=None, softmax_scale=0.0, stream=None):
+    """One decoding step over a cache returned by meda_compress (plus rows appended since)."""
+    L, Hq, d = q.shape
+    Hkv = cache.n_kv_heads
+    n_new = 0 if k_new is None else k_new.shape[2]
+    params = make_decode_params(L, Hq, Hkv, d, int(cache.k_out.shape[0]) // Hkv, q.dtype, n_new, softmax_scale)
+    return Decoder(params, q.device)(q, cache.k_out, cache.v_out, cache.layer_len, cache.layer_off, k_new, v_new,
+                                     stream)

@@ -1,0 +1,338 @@
+// One decoding step over the ragged compressed cache: out = Softmax(q K^T / sqrt(d)) V per layer and
+// query head (Section 3.1, "Decoding with Multimodal KV Cache"), the cache being the rows the
+// compression pass kept for the layer (S_l per kv head, Section 3.2) followed by the rows appended
+// since (K = [K, k_t], V = [V, v_t]).
+//
+// The step reads every cached key and value once and does 4*G*d flops per (key, value) pair, so for
+// the group sizes of the workloads it is bound by HBM: the kernels are plain streaming kernels (no
+// LDS staging of the cache, no matrix unit).  The rows of one (layer, kv head) are cut into NS
+// equal chunks; one workgroup takes one chunk for all G query heads of the group (flash-decoding
+// style: a running maximum, normaliser and weighted value sum per head), a second small kernel merges
+// the chunks.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/meda.h"
+#include "device_utils.hpp"
+
+namespace meda {
+
+constexpr int kDecThreads = 256;
+constexpr int kDecWaves = kDecThreads / 64;
+constexpr int kDecRowsPerGroup = 128;  // rows a workgroup should get at the average layer budget
+constexpr int kDecMaxSplit = 64;
+
+struct DecodeArgs {
+  const char* q;            // [L][Hq][d]
+  const char* k_cache;      // ragged, layer l at row off[l]*Hkv: [Hkv][S_l][d]
+  const char* v_cache;
+  const int32_t* layer_len; // [L]   S_l
+  const int64_t* layer_off; // [L+1]
+  const char* k_new;        // [L][Hkv][n_new][d] or null
+  const char* v_new;
+  char* out;                // [L][Hq][d]
+  float* part;              // [L][Hq][NP][d + 2]: weighted value sum, maximum (base-2 logits), normaliser
+  int L, Hq, Hkv, G, n_new;
+  int NS, NSN, NP;          // chunks of the cached rows, chunks of the appended rows, NS + NSN
+  float scale_log2;
+};
+
+template <typename T>
+struct Elems;
+template <>
+struct Elems<bf16_t> {
+  static constexpr int kPerPiece = 8;
+  static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[8]) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(w[i] << 16);
+      f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ void store(char* dst, float x) {
+    *reinterpret_cast<uint16_t*>(dst) = (uint16_t)float_to_bf16_rne(x);
+  }
+};
+template <>
+struct Elems<float> {
+  static constexpr int kPerPiece = 4;
+  static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[4]) {
+    f[0] = __uint_as_float(v.x);
+    f[1] = __uint_as_float(v.y);
+    f[2] = __uint_as_float(v.z);
+    f[3] = __uint_as_float(v.w);
+  }
+  static __device__ __forceinline__ void store(char* dst, float x) { *reinterpret_cast<float*>(dst) = x; }
+};
+
+// grid (NP, Hkv, L), 256 threads.  A row is read by LPR = row bytes / 16 lanes (16 bytes each), so a
+// wave takes 64 / LPR rows per step; every lane group keeps, per query head of the group, the running
+// maximum, the normaliser and its piece of the weighted value sum over the rows it has seen.  GP is
+// the group size rounded up to a power of two (heads past G repeat head 0 and are not stored).
+template <typename T, int D, int GP>
+__global__ void __launch_bounds__(kDecThreads) decode_partial_kernel(DecodeArgs a) {
+  using TL = Tile<T, D>;
+  using EL = Elems<T>;
+  constexpr int LPR = TL::kChunksPerRow;
+  constexpr int MS = 64 / LPR;
+  constexpr int E = EL::kPerPiece;
+  constexpr int U = 2;  // steps whose loads are issued together
+  __shared__ float red_o[kDecWaves][GP][D];
+  __shared__ float red_m[kDecWaves][GP], red_z[kDecWaves][GP];
+
+  const int sp = blockIdx.x, g = blockIdx.y, l = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int sub = lane / LPR, cc = lane - sub * LPR;
+
+  // the rows of this workgroup
+  const char *kb, *vb;
+  int r_beg, r_end;
+  if (sp < a.NS) {
+    const int S = a.layer_len[l];
+    const int chunk = (S + a.NS - 1) / a.NS;
+    r_beg = sp * chunk;
+    r_end = min(S, r_beg + chunk);
+    const size_t base = ((size_t)a.layer_off[l] * a.Hkv + (size_t)g * S) * TL::kRowBytes;
+    kb = a.k_cache + base;
+    vb = a.v_cache + base;
+  } else {
+    const int chunk = (a.n_new + a.NSN - 1) / a.NSN;
+    r_beg = (sp - a.NS) * chunk;
+    r_end = min(a.n_new, r_beg + chunk);
+    const size_t base = ((size_t)(l * a.Hkv + g) * a.n_new) * TL::kRowBytes;
+    kb = a.k_new + base;
+    vb = a.v_new + base;
+  }
+  kb += cc * 16;
+  vb += cc * 16;
+
+  // this lane's piece of the G queries
+  float qf[GP][E];
+#pragma unroll
+  for (int h = 0; h < GP; ++h) {
+    const int hq = g * a.G + (h < a.G ? h : 0);
+    const uint4 v = *reinterpret_cast<const uint4*>(a.q + ((size_t)(l * a.Hq + hq)) * TL::kRowBytes + cc * 16);
+    EL::unpack(v, qf[h]);
+  }
+  float m[GP], z[GP], o[GP][E];
+#pragma unroll
+  for (int h = 0; h < GP; ++h) {
+    m[h] = kNegBig;
+    z[h] = 0.f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) o[h][e] = 0.f;
+  }
+
+  for (int r0 = r_beg + wave * MS; r0 < r_end; r0 += U * kDecWaves * MS) {
+    uint4 kv[U], vv[U];
+    bool ok[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int r = r0 + u * kDecWaves * MS + sub;
+      ok[u] = r < r_end;
+      const size_t ro = (size_t)min(r, r_end - 1) * TL::kRowBytes;  // rows past the end repeat the last one
+      kv[u] = load16_stream(kb + ro);
+      vv[u] = load16_stream(vb + ro);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float kf[E], vf[E];
+      EL::unpack(kv[u], kf);
+      EL::unpack(vv[u], vf);
+      float s[GP];
+#pragma unroll
+      for (int h = 0; h < GP; ++h) {
+        float d = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) d = fmaf(qf[h][e], kf[e], d);
+#pragma unroll
+        for (int x = LPR / 2; x > 0; x >>= 1) d += __shfl_xor(d, x, kWave);  // sum over the lanes of the row
+        s[h] = ok[u] ? d * a.scale_log2 : kNegBig;
+      }
+      // a new maximum of some head in some lane group: rescale what that head has so far (rare after
+      // the first rows)
+      bool grew = false;
+#pragma unroll
+      for (int h = 0; h < GP; ++h) grew |= s[h] > m[h];
+      if (__ballot(grew) != 0ull) {
+#pragma unroll
+        for (int h = 0; h < GP; ++h) {
+          const float mn = fmaxf(m[h], s[h]);
+          const float c = __builtin_amdgcn_exp2f(m[h] - mn);
+          z[h] *= c;
+#pragma unroll
+          for (int e = 0; e < E; ++e) o[h][e] *= c;
+          m[h] = mn;
+        }
+      }
+#pragma unroll
+      for (int h = 0; h < GP; ++h) {
+        const float p = ok[u] ? __builtin_amdgcn_exp2f(s[h] - m[h]) : 0.f;
+        z[h] += p;
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[h][e] = fmaf(p, vf[e], o[h][e]);
+      }
+    }
+  }
+
+  // merge the lane groups of the wave (they saw different rows), then the waves through LDS
+#pragma unroll
+  for (int x = LPR; x < 64; x <<= 1) {
+#pragma unroll
+    for (int h = 0; h < GP; ++h) {
+      const float mo = __shfl_xor(m[h], x, kWave), zo = __shfl_xor(z[h], x, kWave);
+      const float mn = fmaxf(m[h], mo);
+      const float c0 = __builtin_amdgcn_exp2f(m[h] - mn), c1 = __builtin_amdgcn_exp2f(mo - mn);
+      z[h] = z[h] * c0 + zo * c1;
+#pragma unroll
+      for (int e = 0; e < E; ++e) o[h][e] = o[h][e] * c0 + __shfl_xor(o[h][e], x, kWave) * c1;
+      m[h] = mn;
+    }
+  }
+  if (sub == 0) {
+#pragma unroll
+    for (int h = 0; h < GP; ++h) {
+#pragma unroll
+      for (int e = 0; e < E; ++e) red_o[wave][h][cc * E + e] = o[h][e];
+      if (cc == 0) {
+        red_m[wave][h] = m[h];
+        red_z[wave][h] = z[h];
+      }
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < a.G * D; i += kDecThreads) {
+    const int h = i / D, j = i - h * D;
+    float mn = red_m[0][h];
+#pragma unroll
+    for (int w = 1; w < kDecWaves; ++w) mn = fmaxf(mn, red_m[w][h]);
+    float zs = 0.f, os = 0.f;
+#pragma unroll
+    for (int w = 0; w < kDecWaves; ++w) {
+      const float c = __builtin_amdgcn_exp2f(red_m[w][h] - mn);
+      zs = fmaf(red_z[w][h], c, zs);
+      os = fmaf(red_o[w][h][j], c, os);
+    }
+    float* dst = a.part + ((size_t)(l * a.Hq + g * a.G + h) * a.NP + sp) * (D + 2);
+    dst[j] = os;
+    if (j == 0) {
+      dst[D] = mn;
+      dst[D + 1] = zs;
+    }
+  }
+}
+
+// grid (Hq, L), D threads: merges the NP chunks of one query head and writes the output row.
+template <typename T, int D>
+__global__ void __launch_bounds__(D) decode_combine_kernel(DecodeArgs a) {
+  const int h = blockIdx.x, l = blockIdx.y, j = threadIdx.x;
+  const float* p = a.part + (size_t)(l * a.Hq + h) * a.NP * (D + 2);
+  float mn = kNegBig;
+  for (int s = 0; s < a.NP; ++s) mn = fmaxf(mn, p[(size_t)s * (D + 2) + D]);
+  float zs = 0.f, os = 0.f;
+  for (int s = 0; s < a.NP; ++s) {
+    const float* ps = p + (size_t)s * (D + 2);
+    const float c = __builtin_amdgcn_exp2f(ps[D] - mn);
+    zs = fmaf(ps[D + 1], c, zs);
+    os = fmaf(ps[j], c, os);
+  }
+  Elems<T>::store(a.out + ((size_t)(l * a.Hq + h) * D + j) * sizeof(T), os / zs);
+}
+
+struct DecodePlan {
+  int L, Hq, Hkv, G, GP, d, dtype, n_new, NS, NSN, NP;
+  float scale_log2;
+  size_t ws_bytes;
+};
+
+static meda_status make_decode_plan(const meda_decode_params* p, DecodePlan* pl) {
+  if (!p) return MEDA_ERR_INVALID_ARG;
+  if (p->n_layers < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1 || p->n_new < 0) return MEDA_ERR_INVALID_ARG;
+  if (p->n_q_heads % p->n_kv_heads != 0) return MEDA_ERR_INVALID_ARG;
+  if (p->total_budget < p->n_layers) return MEDA_ERR_BUDGET;  // every layer keeps at least one row
+  if (!(p->softmax_scale >= 0.0f)) return MEDA_ERR_INVALID_ARG;
+  if (p->dtype != MEDA_F32 && p->dtype != MEDA_BF16) return MEDA_ERR_UNSUPPORTED;
+  if (p->head_dim != 64 && p->head_dim != 128) return MEDA_ERR_UNSUPPORTED;
+  const int G = p->n_q_heads / p->n_kv_heads;
+  if (G > 8 || p->n_layers > 65535 || p->n_kv_heads > 65535) return MEDA_ERR_UNSUPPORTED;
+  pl->L = p->n_layers; pl->Hq = p->n_q_heads; pl->Hkv = p->n_kv_heads; pl->G = G; pl->d = p->head_dim;
+  pl->GP = G <= 1 ? 1 : (G <= 2 ? 2 : (G <= 4 ? 4 : 8));
+  pl->dtype = p->dtype; pl->n_new = p->n_new;
+  const int64_t avg = p->total_budget / p->n_layers;
+  int64_t ns = (avg + kDecRowsPerGroup - 1) / kDecRowsPerGroup;
+  pl->NS = (int)(ns < 1 ? 1 : (ns > kDecMaxSplit ? kDecMaxSplit : ns));
+  int64_t nsn = ((int64_t)p->n_new + kDecRowsPerGroup - 1) / kDecRowsPerGroup;
+  pl->NSN = (int)(nsn > kDecMaxSplit ? kDecMaxSplit : nsn);
+  pl->NP = pl->NS + pl->NSN;
+  const double scale = p->softmax_scale > 0.0f ? (double)p->softmax_scale : 1.0 / sqrt((double)p->head_dim);
+  pl->scale_log2 = (float)(scale * 1.4426950408889634074);
+  pl->ws_bytes = ((size_t)pl->L * pl->Hq * pl->NP * (pl->d + 2) * sizeof(float) + 255) / 256 * 256;
+  return MEDA_OK;
+}
+
+template <typename T, int D, int GP>
+static hipError_t launch_decode_g(const DecodePlan& pl, const DecodeArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL((decode_partial_kernel<T, D, GP>), dim3(pl.NP, pl.Hkv, pl.L), dim3(kDecThreads), 0, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(pl.Hq, pl.L), dim3(D), 0, s, a);
+  return hipGetLastError();
+}
+
+template <typename T, int D>
+static hipError_t launch_decode_t(const DecodePlan& pl, const DecodeArgs& a, hipStream_t s) {
+  switch (pl.GP) {
+    case 1: return launch_decode_g<T, D, 1>(pl, a, s);
+    case 2: return launch_decode_g<T, D, 2>(pl, a, s);
+    case 4: return launch_decode_g<T, D, 4>(pl, a, s);
+    default: return launch_decode_g<T, D, 8>(pl, a, s);
+  }
+}
+
+}  // namespace meda
+
+extern "C" {
+
+size_t meda_decode_workspace_bytes(const meda_decode_params* params) {
+  meda::DecodePlan pl;
+  return meda::make_decode_plan(params, &pl) == MEDA_OK ? pl.ws_bytes : 0;
+}
+
+meda_status meda_decode_attention(const meda_decode_params* params, const void* q, const void* k_cache,
+                                  const void* v_cache, const int32_t* layer_len, const int64_t* layer_off,
+                                  const void* k_new, const void* v_new, void* out, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream) {
+  using namespace meda;
+  DecodePlan pl;
+  const meda_status st = make_decode_plan(params, &pl);
+  if (st != MEDA_OK) return st;
+  if (!q || !k_cache || !v_cache || !layer_len || !layer_off || !out) return MEDA_ERR_INVALID_ARG;
+  if (pl.n_new > 0 && (!k_new || !v_new)) return MEDA_ERR_INVALID_ARG;
+  const uintptr_t al = (uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)k_new | (uintptr_t)v_new;
+  if (al & 15u) return MEDA_ERR_INVALID_ARG;  // rows are moved in 16-byte pieces
+  if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < pl.ws_bytes) return MEDA_ERR_WORKSPACE;
+
+  DecodeArgs a;
+  a.q = static_cast<const char*>(q);
+  a.k_cache = static_cast<const char*>(k_cache);
+  a.v_cache = static_cast<const char*>(v_cache);
+  a.layer_len = layer_len;
+  a.layer_off = layer_off;
+  a.k_new = static_cast<const char*>(k_new);
+  a.v_new = static_cast<const char*>(v_new);
+  a.out = static_cast<char*>(out);
+  a.part = static_cast<float*>(workspace);
+  a.L = pl.L; a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.n_new = pl.n_new;
+  a.NS = pl.NS; a.NSN = pl.NSN; a.NP = pl.NP;
+  a.scale_log2 = pl.scale_log2;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (pl.dtype == MEDA_BF16) e = pl.d == 128 ? launch_decode_t<bf16_t, 128>(pl, a, s) : launch_decode_t<bf16_t, 64>(pl, a, s);
+  else e = pl.d == 128 ? launch_decode_t<float, 128>(pl, a, s) : launch_decode_t<float, 64>(pl, a, s);
+  return e == hipSuccess ? MEDA_OK : MEDA_ERR_HIP;
+}
+
+}  // extern "C"

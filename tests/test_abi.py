@@ -107,3 +107,30 @@ def test_profile_mode_range(lib):
     assert lib.meda_profile_enable(-1) == 1 and lib.meda_profile_enable(2 + pkg.N_PHASES) == 1
     ms, calls = pkg.meda_profile_read(reset=True)
     assert calls == 0 and all(m == 0.0 for m in ms)
+
+
+def test_decode_workspace_and_argument_checks(lib):
+    p = pkg.make_decode_params(4, 8, 2, 128, 4 * 250, torch.bfloat16, n_new=3)
+    need = pkg.meda_decode_workspace_bytes(p)
+    assert need > 0 and need % 256 == 0
+    assert ctypes.sizeof(pkg.MedaDecodeParams) == 40 and pkg.MedaDecodeParams.total_budget.offset == 24
+    for bad in (dict(n_layers=0), dict(n_q_heads=7), dict(head_dim=96), dict(n_new=-1), dict(total_budget=3),
+                dict(n_q_heads=18, n_kv_heads=2), dict(dtype=5)):
+        kw = dict(n_layers=4, n_q_heads=8, n_kv_heads=2, head_dim=128, total_budget=1000, dtype=torch.bfloat16)
+        kw.update(bad)
+        assert pkg.meda_decode_workspace_bytes(pkg.make_decode_params(**kw)) == 0, bad
+    fake = 0x10000   # never dereferenced: every case below fails validation on the host
+    def call(params, ptrs, ws_bytes):
+        args = [ctypes.byref(params)] + [ctypes.c_void_p(x) for x in ptrs] + [ctypes.c_size_t(ws_bytes), None]
+        return lib.meda_decode_attention(*args)
+    good = [fake] * 9                                  # q, k, v, len, off, k_new, v_new, out, workspace
+    for i in (0, 1, 2, 3, 4, 5, 6, 7):
+        ptrs = list(good); ptrs[i] = 0
+        assert call(p, ptrs, need) == 1, i             # required pointers (appended rows: n_new > 0)
+    ptrs = list(good); ptrs[8] = 0
+    assert call(p, ptrs, need) == 4 and call(p, good, need - 1) == 4
+    ptrs = list(good); ptrs[1] = fake + 8
+    assert call(p, ptrs, need) == 1                    # cache not 16-byte aligned
+    p0 = pkg.make_decode_params(4, 8, 2, 128, 1000, torch.bfloat16, n_new=0)
+    ptrs = list(good); ptrs[5] = 0; ptrs[6] = 0
+    assert call(p0, ptrs, 0) == 4                      # passes the pointer checks, stops at the workspace size
