@@ -65,6 +65,42 @@ def measured_traffic(workload, kernel):
     return None
 
 
+def decode_step_record(pkg, torch, wl, out, q_dtype, k, v, dev, iters=50):
+    """The step that follows the compression pass (Section 3.1 of the paper: one decoding query per layer and
+    head attends over the cache): its time over the compressed cache of this run and over the full cache,
+    with the HBM rate on the bytes it has to read (every cached key and value once)."""
+    L, Hq, Hkv, d, T = wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.seq_len
+    e = 2 if wl.dtype == "bf16" else 4
+    g = torch.Generator().manual_seed(wl.seed + 1)
+    q = torch.randn(L, Hq, d, generator=g).to(q_dtype).to(dev)
+
+    def timed(dec, *args):
+        for _ in range(3):
+            dec(*args)
+        torch.cuda.synchronize()
+        t0 = torch.cuda.Event(enable_timing=True); t1 = torch.cuda.Event(enable_timing=True)
+        t0.record()
+        for _ in range(iters):
+            dec(*args)
+        t1.record(); torch.cuda.synchronize()
+        return t0.elapsed_time(t1) / iters
+
+    dec = pkg.Decoder(pkg.make_decode_params(L, Hq, Hkv, d, wl.total_budget, q_dtype), dev)
+    ms_c = timed(dec, q, out.k_out, out.v_out, out.layer_len, out.layer_off)
+    # the uncompressed cache [L][Hkv][T][d] is the same layout with S_l = T
+    full_len = torch.full((L,), T, dtype=torch.int32, device=dev)
+    full_off = (torch.arange(L + 1, dtype=torch.int64) * T).to(dev)
+    dec_f = pkg.Decoder(pkg.make_decode_params(L, Hq, Hkv, d, L * T, q_dtype), dev)
+    ms_f = timed(dec_f, q, k.view(-1, d), v.view(-1, d), full_len, full_off)
+    bytes_c = 2.0 * wl.total_budget * Hkv * d * e
+    bytes_f = 2.0 * L * T * Hkv * d * e
+    return {"compressed_ms": ms_c, "compressed_GBps": bytes_c / (ms_c * 1e-3) / 1e9,
+            "compressed_hbm_frac": bytes_c / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "full_cache_ms": ms_f, "full_cache_GBps": bytes_f / (ms_f * 1e-3) / 1e9,
+            "full_cache_hbm_frac": bytes_f / (ms_f * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "speedup": ms_f / ms_c, "cache_bytes_ratio": bytes_c / bytes_f}
+
+
 def cpu_baseline(wl, seconds_target=20.0):
     """The fp64 oracle on a bounded sample: the first n layers of the same workload with the budget
     scaled to n layers, n chosen from a one-layer probe so the run takes roughly ``seconds_target``."""
@@ -103,6 +139,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llava7b_multi_image")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decoding-step measurement")
     ap.add_argument("--no-phase-events", action="store_true",
                     help="do not record per-kernel HIP events inside the timed region")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
@@ -195,6 +232,8 @@ def main():
         "phase_ms_warmup": per_phase,
         "roofline": roofline,
     }
+    if not args.no_decode:
+        rec["decode_step"] = decode_step_record(pkg, torch, wl, out, q.dtype, k, v, dev)
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(rec))

@@ -20,7 +20,7 @@ namespace meda {
 
 constexpr int kDecThreads = 256;
 constexpr int kDecWaves = kDecThreads / 64;
-constexpr int kDecRowsPerGroup = 128;  // rows a workgroup should get at the average layer budget
+constexpr int kDecRowsPerGroup = 128;  // rows a workgroup should get at the average layer budget, per query head of the group (up to 4)
 constexpr int kDecMaxSplit = 64;
 
 struct DecodeArgs {
@@ -51,6 +51,16 @@ struct Elems<bf16_t> {
       f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
     }
   }
+  // sum of the 8 products of two packed pieces (packed dot instruction: exact products, fp32 sums)
+  static __device__ __forceinline__ float dot(const uint4& a, const uint4& b) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const uint32_t x[4] = {a.x, a.y, a.z, a.w}, y[4] = {b.x, b.y, b.z, b.w};
+    float d = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, x[i]), __builtin_bit_cast(bf16x2_t, y[i]), d, false);
+    return d;
+  }
   static __device__ __forceinline__ void store(char* dst, float x) {
     *reinterpret_cast<uint16_t*>(dst) = (uint16_t)float_to_bf16_rne(x);
   }
@@ -64,15 +74,79 @@ struct Elems<float> {
     f[2] = __uint_as_float(v.z);
     f[3] = __uint_as_float(v.w);
   }
+  static __device__ __forceinline__ float dot(const uint4& a, const uint4& b) {
+    float d = __uint_as_float(a.x) * __uint_as_float(b.x);
+    d = fmaf(__uint_as_float(a.y), __uint_as_float(b.y), d);
+    d = fmaf(__uint_as_float(a.z), __uint_as_float(b.z), d);
+    return fmaf(__uint_as_float(a.w), __uint_as_float(b.w), d);
+  }
   static __device__ __forceinline__ void store(char* dst, float x) { *reinterpret_cast<float*>(dst) = x; }
 };
+
+// The LPR lanes that read one row each hold, for every query head of the group, a partial dot product.
+// row_reduce_scatter sums them over the lanes and leaves in v[0] the total of ONE head per lane (the
+// head row_head() names: the upper lane-index bits choose it), at GP + log2(LPR) - 1 exchanges instead
+// of GP * log2(LPR); row_all_gather is the inverse: from one value per lane for that lane's head to all
+// GP values in every lane.
+template <int GP, int LPR>
+__device__ __forceinline__ void row_reduce_scatter(float (&v)[GP], int cc) {
+  int n = GP;
+#pragma unroll
+  for (int x = LPR / 2; x >= 1; x >>= 1) {
+    if (n > 1) {
+      const bool up = (cc & x) != 0;
+      n >>= 1;
+#pragma unroll
+      for (int i = 0; i < GP / 2; ++i) {
+        if (i < n) {
+          const float keep = up ? v[i + n] : v[i], send = up ? v[i] : v[i + n];
+          v[i] = keep + __shfl_xor(send, x, kWave);
+        }
+      }
+    } else {
+      v[0] += __shfl_xor(v[0], x, kWave);
+    }
+  }
+}
+template <int GP, int LPR>
+__device__ __forceinline__ int row_head(int cc) {
+  int h = 0, n = GP;
+#pragma unroll
+  for (int x = LPR / 2; x >= 1; x >>= 1) {
+    if (n > 1) {
+      n >>= 1;
+      h += (cc & x) ? n : 0;
+    }
+  }
+  return h;
+}
+template <int GP, int LPR>
+__device__ __forceinline__ void row_all_gather(float mine, float (&w)[GP], int cc) {
+  w[0] = mine;
+  constexpr int kSteps = GP == 1 ? 0 : (GP == 2 ? 1 : (GP == 4 ? 2 : 3));
+  int n = 1;
+#pragma unroll
+  for (int st = kSteps - 1; st >= 0; --st) {
+    const int x = (LPR / 2) >> st;  // the exchange distances of the halving steps, last one first
+    const bool up = (cc & x) != 0;
+#pragma unroll
+    for (int i = 0; i < GP / 2; ++i) {
+      if (i < n) {
+        const float other = __shfl_xor(w[i], x, kWave);
+        w[i + n] = up ? w[i] : other;
+        w[i] = up ? other : w[i];
+      }
+    }
+    n <<= 1;
+  }
+}
 
 // grid (NP, Hkv, L), 256 threads.  A row is read by LPR = row bytes / 16 lanes (16 bytes each), so a
 // wave takes 64 / LPR rows per step; every lane group keeps, per query head of the group, the running
 // maximum, the normaliser and its piece of the weighted value sum over the rows it has seen.  GP is
 // the group size rounded up to a power of two (heads past G repeat head 0 and are not stored).
 template <typename T, int D, int GP>
-__global__ void __launch_bounds__(kDecThreads) decode_partial_kernel(DecodeArgs a) {
+__global__ void __launch_bounds__(kDecThreads, 2) decode_partial_kernel(DecodeArgs a) {
   using TL = Tile<T, D>;
   using EL = Elems<T>;
   constexpr int LPR = TL::kChunksPerRow;
@@ -109,22 +183,19 @@ __global__ void __launch_bounds__(kDecThreads) decode_partial_kernel(DecodeArgs 
   kb += cc * 16;
   vb += cc * 16;
 
-  // this lane's piece of the G queries
-  float qf[GP][E];
+  // this lane's piece of the G queries, kept packed
+  uint4 qp[GP];
 #pragma unroll
   for (int h = 0; h < GP; ++h) {
     const int hq = g * a.G + (h < a.G ? h : 0);
-    const uint4 v = *reinterpret_cast<const uint4*>(a.q + ((size_t)(l * a.Hq + hq)) * TL::kRowBytes + cc * 16);
-    EL::unpack(v, qf[h]);
+    qp[h] = *reinterpret_cast<const uint4*>(a.q + ((size_t)(l * a.Hq + hq)) * TL::kRowBytes + cc * 16);
   }
-  float m[GP], z[GP], o[GP][E];
+  // running maximum and normaliser of the ONE head this lane evaluates (row_head), weighted value sums of all
+  float m1 = kNegBig, z1 = 0.f, o[GP][E];
 #pragma unroll
-  for (int h = 0; h < GP; ++h) {
-    m[h] = kNegBig;
-    z[h] = 0.f;
+  for (int h = 0; h < GP; ++h)
 #pragma unroll
     for (int e = 0; e < E; ++e) o[h][e] = 0.f;
-  }
 
   for (int r0 = r_beg + wave * MS; r0 < r_end; r0 += U * kDecWaves * MS) {
     uint4 kv[U], vv[U];
@@ -139,44 +210,39 @@ __global__ void __launch_bounds__(kDecThreads) decode_partial_kernel(DecodeArgs 
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float kf[E], vf[E];
-      EL::unpack(kv[u], kf);
-      EL::unpack(vv[u], vf);
       float s[GP];
 #pragma unroll
-      for (int h = 0; h < GP; ++h) {
-        float d = 0.f;
-#pragma unroll
-        for (int e = 0; e < E; ++e) d = fmaf(qf[h][e], kf[e], d);
-#pragma unroll
-        for (int x = LPR / 2; x > 0; x >>= 1) d += __shfl_xor(d, x, kWave);  // sum over the lanes of the row
-        s[h] = ok[u] ? d * a.scale_log2 : kNegBig;
-      }
+      for (int h = 0; h < GP; ++h) s[h] = EL::dot(qp[h], kv[u]);
+      row_reduce_scatter<GP, LPR>(s, cc);
+      const float s1 = ok[u] ? s[0] * a.scale_log2 : kNegBig;
       // a new maximum of some head in some lane group: rescale what that head has so far (rare after
       // the first rows)
-      bool grew = false;
+      if (__ballot(s1 > m1) != 0ull) {
+        const float mn = fmaxf(m1, s1);
+        const float c1 = __builtin_amdgcn_exp2f(m1 - mn);
+        z1 *= c1;
+        m1 = mn;
+        float c[GP];
+        row_all_gather<GP, LPR>(c1, c, cc);
 #pragma unroll
-      for (int h = 0; h < GP; ++h) grew |= s[h] > m[h];
-      if (__ballot(grew) != 0ull) {
+        for (int h = 0; h < GP; ++h)
 #pragma unroll
-        for (int h = 0; h < GP; ++h) {
-          const float mn = fmaxf(m[h], s[h]);
-          const float c = __builtin_amdgcn_exp2f(m[h] - mn);
-          z[h] *= c;
-#pragma unroll
-          for (int e = 0; e < E; ++e) o[h][e] *= c;
-          m[h] = mn;
-        }
+          for (int e = 0; e < E; ++e) o[h][e] *= c[h];
       }
+      const float p1 = ok[u] ? __builtin_amdgcn_exp2f(s1 - m1) : 0.f;
+      z1 += p1;
+      float p[GP], vf[E];
+      row_all_gather<GP, LPR>(p1, p, cc);
+      EL::unpack(vv[u], vf);
 #pragma unroll
-      for (int h = 0; h < GP; ++h) {
-        const float p = ok[u] ? __builtin_amdgcn_exp2f(s[h] - m[h]) : 0.f;
-        z[h] += p;
+      for (int h = 0; h < GP; ++h)
 #pragma unroll
-        for (int e = 0; e < E; ++e) o[h][e] = fmaf(p, vf[e], o[h][e]);
-      }
+        for (int e = 0; e < E; ++e) o[h][e] = fmaf(p[h], vf[e], o[h][e]);
     }
   }
+  float m[GP], z[GP];
+  row_all_gather<GP, LPR>(m1, m, cc);
+  row_all_gather<GP, LPR>(z1, z, cc);
 
   // merge the lane groups of the wave (they saw different rows), then the waves through LDS
 #pragma unroll
@@ -261,8 +327,10 @@ static meda_status make_decode_plan(const meda_decode_params* p, DecodePlan* pl)
   pl->L = p->n_layers; pl->Hq = p->n_q_heads; pl->Hkv = p->n_kv_heads; pl->G = G; pl->d = p->head_dim;
   pl->GP = G <= 1 ? 1 : (G <= 2 ? 2 : (G <= 4 ? 4 : 8));
   pl->dtype = p->dtype; pl->n_new = p->n_new;
+  // the per-head state a workgroup merges at its end grows with the group size: give it more rows then
+  const int rows_per_group = kDecRowsPerGroup * (pl->GP < 4 ? pl->GP : 4);
   const int64_t avg = p->total_budget / p->n_layers;
-  int64_t ns = (avg + kDecRowsPerGroup - 1) / kDecRowsPerGroup;
+  int64_t ns = (avg + rows_per_group - 1) / rows_per_group;
   pl->NS = (int)(ns < 1 ? 1 : (ns > kDecMaxSplit ? kDecMaxSplit : ns));
   int64_t nsn = ((int64_t)p->n_new + kDecRowsPerGroup - 1) / kDecRowsPerGroup;
   pl->NSN = (int)(nsn > kDecMaxSplit ? kDecMaxSplit : nsn);
