@@ -166,3 +166,19 @@ def test_phase_timers_all_and_single():
     finally:
         pkg.meda_profile_enable(False)
     assert np.array_equal(a["k_out"], ref["k_out"]) and np.array_equal(b["v_out"], ref["v_out"])
+
+
+def test_many_heads_small_context_both_similarity_kernels():
+    # 8 layers x 32 kv heads = 256 (layer, head) pairs: enough for the resident-set similarity kernel to be used;
+    # the temperature spread puts some layer budgets below and some above what fits into LDS (576 slots), so
+    # both similarity kernels run in this one call
+    layout = (("t", 40, -1), ("v", 576, 0), ("t", 30, -1), ("v", 576, 1), ("t", 58, -1), ("v", 576, 2), ("t", 192, -1))
+    wl = variant(TINY, name="res_and_tiled", n_layers=8, n_q_heads=32, n_kv_heads=32, head_dim=128, dtype="bf16",
+                 layout=layout, window=32, total_budget=8 * 600, tau_lo=0.5, tau_hi=3.0, seed=12)
+    assert wl.seq_len == 2048
+    data = generate(wl)
+    comp, gpu = run_gpu(wl, data)
+    S = gpu["S"]
+    print("budgets", S.tolist(), flush=True)
+    assert (S <= 576).any() and (S > 576).any(), S
+    check_all(wl, data, gpu, heads=[(l, g) for l in range(wl.n_layers) for g in (0, 13, 31)])
