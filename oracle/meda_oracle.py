@@ -410,7 +410,11 @@ def meda_compress(q_win, k, v, mask, total_budget, window, dtype="f32", scale=No
                   recent_num=3, recent_den=4):
     """The whole compression pass on float64 copies of the stored inputs.
 
-    q_win [L, Hq, W, d], k, v [L, Hkv, T, d], mask [T].  Returns a dict with, per layer,
+    q_win [L, Hq, R, d], k, v [L, Hkv, T, d], mask [T].  The R query rows are the last R positions:
+    R = window is the observation-window variant (only the last W positions score the keys), R = T is
+    the scoring as the paper writes it (Section 3.3 sums A_p over all prompt rows, Section 3.2 builds
+    A_TV / A_VT from all text / vision queries); ``window`` stays the lower bound of the recent part and
+    of every layer budget either way.  Returns a dict with, per layer,
     entropies (h_tv, h_vt, e_cm), budgets (S, M, N, off), the column scores and, per
     (layer, kv head), index sets, assignments and merged rows; plus the ragged outputs
     ``k_out`` / ``v_out`` as lists over layers of [Hkv, S_l, d] arrays.
@@ -420,7 +424,7 @@ def meda_compress(q_win, k, v, mask, total_budget, window, dtype="f32", scale=No
     v = np.asarray(v, dtype=F64)
     mask = np.asarray(mask)
     L, Hkv, T, d = k.shape
-    assert q_win.shape[2] == window
+    assert q_win.shape[2] in (window, T), "query rows: the observation window or every prompt position"
     a_s = []
     ent = np.zeros((L, 3), dtype=F64)
     for l in range(L):

@@ -32,10 +32,16 @@ class Workload:
     drift_sigma: float = 0.0       # >0: group g's centres = group g-1's + N(0, drift_sigma^2)
     recent_num: int = 3            # recent : important = 3 : 1 (Section 4.3)
     recent_den: int = 4
+    score_rows: int = 0            # query rows that score the keys: 0 = the observation window (last W
+                                   # positions); seq_len = every prompt position, as the paper writes it
 
     @property
     def seq_len(self) -> int:
         return sum(s[1] for s in self.layout)
+
+    @property
+    def n_score_rows(self) -> int:
+        return self.score_rows if self.score_rows > 0 else self.window
 
     @property
     def n_text(self) -> int:

@@ -51,12 +51,13 @@ def layer_taus(wl: Workload) -> np.ndarray:
 
 
 def generate_layer(wl: Workload, layer: int):
-    """float32 arrays (q [Hq,W,d], k [Hkv,T,d], v [Hkv,T,d]) of one layer, before the storage cast."""
-    T, W, d = wl.seq_len, wl.window, wl.head_dim
+    """float32 arrays (q [Hq,R,d], k [Hkv,T,d], v [Hkv,T,d]) of one layer, before the storage cast; R query
+    rows = the last R positions (the observation window, or all T positions)."""
+    T, W, d, R = wl.seq_len, wl.window, wl.head_dim, wl.n_score_rows
     Hq, Hkv, G = wl.n_q_heads, wl.n_kv_heads, wl.group_size
     tau = np.float32(layer_taus(wl)[layer])
 
-    q = _rng(wl.seed, layer, _T_Q).standard_normal((Hq, W, d), dtype=np.float32) * tau
+    q = _rng(wl.seed, layer, _T_Q).standard_normal((Hq, R, d), dtype=np.float32) * tau
     k = _rng(wl.seed, layer, _T_K).standard_normal((Hkv, T, d), dtype=np.float32)
     v = _rng(wl.seed, layer, _T_V).standard_normal((Hkv, T, d), dtype=np.float32)
 
@@ -81,7 +82,7 @@ def generate_layer(wl: Workload, layer: int):
     if n_heavy > 0:
         heavy = np.sort(_rng(wl.seed, layer, _T_HEAVY).choice(T, size=n_heavy, replace=False))
         for g in range(Hkv):
-            qbar = q[g * G:(g + 1) * G].reshape(-1, d).mean(axis=0)
+            qbar = q[g * G:(g + 1) * G, R - W:].reshape(-1, d).mean(axis=0)   # mean query of the last W positions
             direction = qbar / max(float(np.linalg.norm(qbar)), 1e-20)
             k[g, heavy] = (3.0 * np.sqrt(np.float32(d))) * direction.astype(np.float32)
     return q, k, v
@@ -95,15 +96,15 @@ def generate(wl: Workload, layers: Optional[Iterable[int]] = None, threads: int 
              ) -> Dict[str, object]:
     """Inputs of ``wl`` as CPU torch tensors in the workload's storage type.
 
-    Returns ``{"q": [L,Hq,W,d], "k": [L,Hkv,T,d], "v": [L,Hkv,T,d], "mask": uint8 [T]}``.
+    Returns ``{"q": [L,Hq,R,d] (R = W, or T when the workload scores with every prompt row), "k": [L,Hkv,T,d], "v": [L,Hkv,T,d], "mask": uint8 [T]}``.
     ``layers`` restricts generation to a subset (the tensors then hold only those layers,
     in the given order).
     """
     layer_list = list(range(wl.n_layers)) if layers is None else list(layers)
     n = len(layer_list)
     dt = storage_dtype(wl)
-    T, W, d = wl.seq_len, wl.window, wl.head_dim
-    q = torch.empty((n, wl.n_q_heads, W, d), dtype=dt)
+    T, d = wl.seq_len, wl.head_dim
+    q = torch.empty((n, wl.n_q_heads, wl.n_score_rows, d), dtype=dt)
     k = torch.empty((n, wl.n_kv_heads, T, d), dtype=dt)
     v = torch.empty((n, wl.n_kv_heads, T, d), dtype=dt)
 
