@@ -44,6 +44,10 @@ typedef enum { MEDA_F32 = 0, MEDA_BF16 = 1 } meda_dtype;
 /* flags */
 #define MEDA_FLAG_UNIFORM_BUDGET 1 /* skip the entropy softmax: S_l = B/L (+1 on the lowest layers)  */
 #define MEDA_FLAG_NO_MERGE 2       /* evict instead of merge: conserved rows are copied unchanged    */
+#define MEDA_FLAG_FULL_PROMPT 4    /* every prompt position scores the keys (Section 3.3 sums A_p over all
+                                      prompt rows, Section 3.2 takes all text / vision queries): q_win
+                                      is then [L][Hq][T][d]; `window` stays the lower bound of the recent
+                                      part and of the layer budgets; needs Hq / Hkv <= 8                */
 
 typedef struct {
   int32_t n_layers;     /* L, 1..256                                                               */

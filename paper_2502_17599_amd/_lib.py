@@ -18,6 +18,7 @@ REGIONS = {"col_scores": 0, "inv_norm": 1, "row_stats": 2, "alloc": 3, "less_idx
 N_PHASES = 8
 FLAG_UNIFORM_BUDGET = 1
 FLAG_NO_MERGE = 2
+FLAG_FULL_PROMPT = 4
 _DTYPES = {torch.float32: 0, torch.bfloat16: 1}
 
 
@@ -192,7 +193,8 @@ class Compressor:
                  stream: Optional[torch.cuda.Stream] = None) -> CompressedCache:
         p = self.params
         dt = {0: torch.float32, 1: torch.bfloat16}[p.dtype]
-        for name, t, shape in (("q_win", q_win, (p.n_layers, p.n_q_heads, p.window, p.head_dim)),
+        q_rows = p.seq_len if (p.flags & FLAG_FULL_PROMPT) else p.window
+        for name, t, shape in (("q_win", q_win, (p.n_layers, p.n_q_heads, q_rows, p.head_dim)),
                                ("k", k, (p.n_layers, p.n_kv_heads, p.seq_len, p.head_dim)),
                                ("v", v, (p.n_layers, p.n_kv_heads, p.seq_len, p.head_dim))):
             if tuple(t.shape) != shape or t.dtype != dt or not t.is_contiguous() or t.device != self.device:

@@ -15,7 +15,7 @@ struct AllocArgs {
   int32_t* layer_len;      // user outputs
   int64_t* layer_off;
   double* entropy;         // may be null
-  int L, NT, T, W, num, den, flags;
+  int L, NT, T, W, R, num, den, flags;   // W: recent window; R: scoring rows (the last R positions)
   long long B;
 };
 
@@ -32,9 +32,11 @@ __global__ void __launch_bounds__(256) allocate_kernel(AllocArgs a) {
   const int tid = threadIdx.x, L = a.L;
   const double lo = (double)min(a.W, a.T), hi = (double)a.T, B = (double)a.B;
 
-  // window rows of each modality (the denominators of the two entropy means)
-  const int n_vis = __syncthreads_count(tid < a.W && a.mask[a.T - a.W + tid] != 0);
-  const int n_text = a.W - n_vis;
+  // scoring rows of each modality (the denominators of the two entropy means)
+  int n_vis = 0;
+  for (int r0 = 0; r0 < a.R; r0 += blockDim.x)
+    n_vis += __syncthreads_count(r0 + tid < a.R && a.mask[a.T - a.R + r0 + tid] != 0);
+  const int n_text = a.R - n_vis;
   // per-tile entropy partials of a layer are summed by one wave (lanes stride over the tiles)
   for (int l = tid >> 6; l < L; l += blockDim.x >> 6) {
     const double* p = a.ent_part + (size_t)l * a.NT * 2;
@@ -320,7 +322,7 @@ hipError_t launch_allocate(const Plan& p, const Buffers& b, hipStream_t s) {
   a.layer_len = b.layer_len;
   a.layer_off = b.layer_off;
   a.entropy = b.entropy;
-  a.L = p.L; a.NT = p.NT; a.T = p.T; a.W = p.W; a.num = p.num; a.den = p.den; a.flags = p.flags;
+  a.L = p.L; a.NT = p.NTk; a.T = p.T; a.W = p.W; a.R = p.R; a.num = p.num; a.den = p.den; a.flags = p.flags;
   a.B = p.B;
   hipLaunchKernelGGL(allocate_kernel, dim3(1), dim3(256), 0, s, a);
   return hipGetLastError();

@@ -11,6 +11,40 @@ namespace meda {
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Tiling of the two scoring passes for w query rows (the last w positions) of a sequence of t keys.
+static bool score_geometry(Plan* pl, int t, int w) {
+  pl->Tb = t;
+  pl->Wb = w;
+  pl->RB = (w + 31) / 32;
+  pl->Wp = pl->RB * 32;
+  const int combos = pl->G * pl->RB;
+  if (combos > 32) return false;
+  pl->NQ = combos <= 4 ? 1 : (combos <= 16 ? 2 : 4);  // (head, row block) pairs a wave keeps in registers
+  pl->NCG = (combos + pl->NQ - 1) / pl->NQ;
+  pl->CS = (pl->NCG <= 4) ? 4 / pl->NCG : 1;
+  const int tiles = (t + kScoreTile - 1) / kScoreTile;
+  pl->NT = tiles;
+  const int64_t units = (int64_t)pl->L * pl->Hkv;
+  int64_t nch = (4096 + units - 1) / units;
+  if (nch < 1) nch = 1;
+  if (nch > tiles) nch = tiles;
+  const int tiles_per_chunk = (int)((tiles + nch - 1) / nch);
+  pl->CH = tiles_per_chunk * kScoreTile;
+  pl->NCH = (t + pl->CH - 1) / pl->CH;
+  pl->NPART = pl->NCH * pl->CS;
+  return true;
+}
+
+Plan score_block_plan(const Plan& whole, int bi) {
+  Plan sub = whole;
+  const int t_eff = whole.Tk - bi * kScoreRowBlock;             // keys the block's last row sees
+  const int w_b = t_eff < kScoreRowBlock ? t_eff : kScoreRowBlock;
+  score_geometry(&sub, t_eff, w_b);                             // cannot fail: not more rows than block 0
+  sub.q_row0 = t_eff - w_b;
+  sub.accumulate = bi > 0;
+  return sub;
+}
+
 meda_status make_plan(const meda_params* p, Plan* out) {
   if (!p) return MEDA_ERR_INVALID_ARG;
   if (p->n_layers < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1 || p->seq_len < 1 || p->window < 1)
@@ -35,32 +69,31 @@ meda_status make_plan(const meda_params* p, Plan* out) {
   const double scale = (p->softmax_scale > 0.0f) ? (double)p->softmax_scale : 1.0 / sqrt((double)pl.d);
   pl.scale_log2 = (float)(scale * 1.4426950408889634074);
 
-  pl.RB = (pl.W + 31) / 32;
-  pl.Wp = pl.RB * 32;
-  const int combos = pl.G * pl.RB;
-  if (combos > 32) return MEDA_ERR_UNSUPPORTED;
-  pl.NQ = combos <= 4 ? 1 : (combos <= 16 ? 2 : 4);  // (head, row block) pairs a wave keeps in registers
-  pl.NCG = (combos + pl.NQ - 1) / pl.NQ;
-  pl.CS = (pl.NCG <= 4) ? 4 / pl.NCG : 1;
-  const int tiles = (pl.T + kScoreTile - 1) / kScoreTile;
-  pl.NT = tiles;
-  const int64_t units = (int64_t)pl.L * pl.Hkv;
-  int64_t nch = (4096 + units - 1) / units;
-  if (nch < 1) nch = 1;
-  if (nch > tiles) nch = tiles;
-  const int tiles_per_chunk = (int)((tiles + nch - 1) / nch);
-  pl.CH = tiles_per_chunk * kScoreTile;
-  pl.NCH = (pl.T + pl.CH - 1) / pl.CH;
-  pl.NPART = pl.NCH * pl.CS;
+  const bool full_prompt = (pl.flags & MEDA_FLAG_FULL_PROMPT) != 0;
+  pl.R = full_prompt ? pl.T : pl.W;
+  pl.n_blocks = full_prompt ? (pl.T + kScoreRowBlock - 1) / kScoreRowBlock : 1;
+  pl.Tk = pl.T;
+  pl.q_row0 = 0;
+  pl.NTk = (pl.T + kScoreTile - 1) / kScoreTile;
+  pl.accumulate = 0;
+  // scoring geometry of the largest block (the only one without the flag); the workspace holds the
+  // row statistics of one block at a time, sized for the block that needs most
+  const int w_score = full_prompt ? (pl.T < kScoreRowBlock ? pl.T : kScoreRowBlock) : pl.W;
+  if (!score_geometry(&pl, pl.T, w_score)) return MEDA_ERR_UNSUPPORTED;
+  int max_wp = pl.Wp, max_npart = pl.NPART;
+  for (int bi = 1; bi < pl.n_blocks; ++bi) {
+    const Plan sub = score_block_plan(pl, bi);
+    if (sub.Wp * sub.NPART > max_wp * max_npart) { max_wp = sub.Wp; max_npart = sub.NPART; }
+  }
 
   pl.n_less_total = (size_t)((int64_t)pl.L * pl.T - pl.B) * pl.Hkv;
   size_t o = 0;
   auto take = [&](size_t bytes) { const size_t at = o; o = align_up(o + bytes, 256); return at; };
-  pl.off_stats_part = take((size_t)pl.L * pl.Hq * pl.Wp * pl.NPART * 16);
+  pl.off_stats_part = take((size_t)pl.L * pl.Hq * max_wp * max_npart * 16);
   pl.off_stats = take((size_t)pl.L * pl.Hq * pl.Wp * 16);
   pl.off_inv_norm = take((size_t)pl.L * pl.Hkv * pl.T * 4);
   pl.off_col_scores = take((size_t)pl.L * pl.Hkv * pl.T * 4);
-  pl.off_ent_part = take((size_t)pl.L * pl.NT * 2 * 8);
+  pl.off_ent_part = take((size_t)pl.L * pl.NTk * 2 * 8);
   pl.off_alloc = take((size_t)pl.L * 16);
   pl.off_layer_off = take((size_t)(pl.L + 1) * 8);
   pl.off_sel_idx = take((size_t)pl.B * pl.Hkv * 4);
@@ -164,7 +197,18 @@ meda_status meda_compress(const meda_params* params, const void* q_win, const vo
   if (prof && ce.only <= 0) err = hipEventRecord(ce.ev[0], s);
   for (int i = 0; i < MEDA_N_PHASES && err == hipSuccess; ++i) {
     const bool skip = no_merge && (i == 5 || i == 6);
-    if (!skip) err = phases[i](pl, b, s);
+    if (i == 0 && pl.n_blocks > 1) {
+      // every prompt row scores: the three scoring kernels run once per row block, last block first (the
+      // first launch stores column scores and entropy partials, the others add); all of it is timed as phase 0
+      for (int bi = 0; bi < pl.n_blocks && err == hipSuccess; ++bi) {
+        const Plan sub = score_block_plan(pl, bi);
+        for (int j = 0; j < 3 && err == hipSuccess; ++j) err = phases[j](sub, b, s);
+      }
+    } else if (i <= 2 && pl.n_blocks > 1) {
+      // done above
+    } else if (!skip) {
+      err = phases[i](pl, b, s);
+    }
     const bool rec = prof && (ce.only < 0 || i == ce.only || i + 1 == ce.only);
     if (rec && err == hipSuccess) err = hipEventRecord(ce.ev[i + 1], s);
   }

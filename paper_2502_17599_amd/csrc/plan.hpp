@@ -16,6 +16,7 @@ constexpr int kSimWaves = 4;
 constexpr int kSimRows = kSimRowsPerWave * kSimWaves;  // less-important rows per workgroup
 constexpr int kSimSlotTile = 64;                       // conserved slots staged in LDS per step
 constexpr int kMaxLayers = 256;
+constexpr int kScoreRowBlock = 128;  // query rows per scoring launch when every prompt row scores
 
 struct Plan {
   // problem
@@ -29,6 +30,17 @@ struct Plan {
   int NQ, NCG, CS;   // pass A: (head, row block) pairs per wave, wave groups, column split
   int CH, NCH, NPART;  // pass A: columns per chunk, chunks, partial statistics per row
   int NT;            // pass B: column tiles
+  // Scoring rows.  Normally the W window rows (R == W).  With MEDA_FLAG_FULL_PROMPT every prompt position
+  // scores (R == T) and the scoring passes run once per block of at most kScoreRowBlock rows, last block
+  // first: a block of rows [q_row0, q_row0 + Wb) sees only the keys below Tb = q_row0 + Wb, so it is the window
+  // computation of a sequence cut after its last row (score_block_plan sets the fields below for one block).
+  int Tb, Wb;        // keys and query rows of this scoring launch (T and W without the flag)
+  int R;             // scoring rows in total; rows per (layer, head) in the query buffer
+  int n_blocks;      // row blocks
+  int Tk;            // key rows per (layer, kv head) in memory (T of the whole sequence)
+  int q_row0;        // first row of the block inside the query buffer
+  int NTk;           // column tiles of the whole sequence (stride of the per-tile entropy partials)
+  int accumulate;    // add to column scores / entropy partials instead of storing (every block but the first)
   // workspace regions (byte offsets)
   size_t off_stats_part, off_stats, off_inv_norm, off_col_scores, off_ent_part, off_alloc, off_layer_off,
       off_sel_idx, off_sel_inv, off_less_idx, off_less_slot, off_sort_a, off_sort_b, off_sort_c, off_sort_d, off_seg_beg, off_seg_end, total_bytes;
@@ -36,6 +48,8 @@ struct Plan {
 };
 
 meda_status make_plan(const meda_params* p, Plan* plan);
+// The plan of scoring block `bi` (0 = the last rows of the prompt) of a plan made by make_plan.
+Plan score_block_plan(const Plan& whole, int bi);
 
 struct Buffers {
   const void *q, *k, *v;

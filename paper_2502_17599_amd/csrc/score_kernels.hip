@@ -23,8 +23,13 @@ struct ScoreArgs {
   float* inv_norm;     // [L][Hkv][T]
   float* col_scores;   // [L][Hkv][T]
   double* ent_part;    // [L][NT][2]
-  int L, Hq, Hkv, G, T, W, RB, Wp;
+  int L, Hq, Hkv, G, T, W, RB, Wp;   // T keys and W query rows of this launch (the last W positions below T)
   int NCG, CS, CH, NPART, NT;
+  int Tk;          // key rows per (layer, kv head) in memory (>= T)
+  int q_rows;      // rows per (layer, head) in the query buffer
+  int q_row0;      // first query row of this launch in the buffer
+  int NTk;         // tiles per layer in ent_part
+  int accumulate;  // add to col_scores / ent_part instead of storing
   float c;             // scale * log2(e)
 };
 
@@ -70,14 +75,14 @@ __global__ void __launch_bounds__(NW * 64, (NQ == 1 && NW == 4 && sizeof(T) == 2
       qhead[q] = g * a.G + hg;
       qrow[q] = rb * 32 + n;
       if (qrow[q] < a.W)
-        frag_load(qf[q], a.q + ((size_t)(l * a.Hq + qhead[q]) * a.W + qrow[q]) * TL::kRowBytes, kg);
+        frag_load(qf[q], a.q + ((size_t)(l * a.Hq + qhead[q]) * a.q_rows + a.q_row0 + qrow[q]) * TL::kRowBytes, kg);
     }
   }
 
   const int jbeg = ch * a.CH;
   const int jend = min(a.T, jbeg + a.CH);
-  const char* kbase = a.k + (size_t)(l * a.Hkv + g) * a.T * TL::kRowBytes;
-  float* invn_out = a.inv_norm + (size_t)(l * a.Hkv + g) * a.T;
+  const char* kbase = a.k + (size_t)(l * a.Hkv + g) * a.Tk * TL::kRowBytes;
+  float* invn_out = a.inv_norm + (size_t)(l * a.Hkv + g) * a.Tk;
 
   TileStage<T, D, kScoreTile, nthr> stage;
   uint8_t mreg = 0;
@@ -248,10 +253,10 @@ __global__ void __launch_bounds__(256, (RB == 1 && sizeof(T) == 2 && !KSTAGE) ? 
   TileStage<T, D, KSTAGE ? kScoreTile : 1> kstage;
   TileStage<T, D, RB * 32> qstage;
   float4 sreg = make_float4(0.f, 0.f, 0.f, 0.f);
-  const char* ktile_src = a.k + ((size_t)l * a.Hkv * a.T + j0) * TL::kRowBytes;
-  const size_t khead_stride = (size_t)a.T * TL::kRowBytes;
+  const char* ktile_src = a.k + ((size_t)l * a.Hkv * a.Tk + j0) * TL::kRowBytes;
+  const size_t khead_stride = (size_t)a.Tk * TL::kRowBytes;
   if (KSTAGE) kstage.template fetch<true>(ktile_src, rows_valid, tid, 256);
-  qstage.fetch(a.q + (size_t)(l * a.Hq) * a.W * TL::kRowBytes, a.W, tid, 256);
+  qstage.fetch(a.q + ((size_t)(l * a.Hq) * a.q_rows + a.q_row0) * TL::kRowBytes, a.W, tid, 256);
   if (tid < Wp) sreg = a.stats[(size_t)(l * a.Hq) * a.Wp + tid];
 
   Frag<T, D> kf;
@@ -279,7 +284,7 @@ __global__ void __launch_bounds__(256, (RB == 1 && sizeof(T) == 2 && !KSTAGE) ? 
     if (h + 1 < a.Hq) {
       const int hn = h + 1;
       if (KSTAGE && hn % a.G == 0) kstage.template fetch<true>(ktile_src + (size_t)(hn / a.G) * khead_stride, rows_valid, tid, 256);
-      qstage.fetch(a.q + (size_t)(l * a.Hq + hn) * a.W * TL::kRowBytes, a.W, tid, 256);
+      qstage.fetch(a.q + ((size_t)(l * a.Hq + hn) * a.q_rows + a.q_row0) * TL::kRowBytes, a.W, tid, 256);
       if (tid < Wp) sreg = a.stats[(size_t)(l * a.Hq + hn) * a.Wp + tid];
     }
     if (hg == 0) {
@@ -315,7 +320,10 @@ __global__ void __launch_bounds__(256, (RB == 1 && sizeof(T) == 2 && !KSTAGE) ? 
     }
     if (hg == a.G - 1) {
       const float tot = colsum + __shfl_xor(colsum, 32, kWave);
-      if (kg == 0 && col_ok) a.col_scores[(size_t)(l * a.Hkv + g) * a.T + j] = tot;
+      if (kg == 0 && col_ok) {
+        float* dst = a.col_scores + (size_t)(l * a.Hkv + g) * a.Tk + j;
+        *dst = a.accumulate ? *dst + tot : tot;  // one writer per column and launch
+      }
     }
   }
 
@@ -340,7 +348,8 @@ __global__ void __launch_bounds__(256, (RB == 1 && sizeof(T) == 2 && !KSTAGE) ? 
   __syncthreads();
   if (tid < 2) {
     const double sum = red[tid] + red[2 + tid] + red[4 + tid] + red[6 + tid];
-    a.ent_part[((size_t)l * a.NT + tile) * 2 + tid] = -sum;
+    double* dst = a.ent_part + ((size_t)l * a.NTk + tile) * 2 + tid;
+    *dst = a.accumulate ? *dst - sum : -sum;
   }
 }
 
@@ -356,7 +365,8 @@ static ScoreArgs make_args(const Plan& p, const Buffers& b) {
   a.inv_norm = reinterpret_cast<float*>(b.ws + p.off_inv_norm);
   a.col_scores = reinterpret_cast<float*>(b.ws + p.off_col_scores);
   a.ent_part = reinterpret_cast<double*>(b.ws + p.off_ent_part);
-  a.L = p.L; a.Hq = p.Hq; a.Hkv = p.Hkv; a.G = p.G; a.T = p.T; a.W = p.W; a.RB = p.RB; a.Wp = p.Wp;
+  a.L = p.L; a.Hq = p.Hq; a.Hkv = p.Hkv; a.G = p.G; a.T = p.Tb; a.W = p.Wb; a.RB = p.RB; a.Wp = p.Wp;
+  a.Tk = p.Tk; a.q_rows = p.R; a.q_row0 = p.q_row0; a.NTk = p.NTk; a.accumulate = p.accumulate;
   a.NCG = p.NCG; a.CS = p.CS; a.CH = p.CH; a.NPART = p.NPART; a.NT = p.NT;
   a.c = p.scale_log2;
   return a;

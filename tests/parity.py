@@ -32,6 +32,8 @@ def run_gpu(wl, data, device="cuda:0", flags=0):
     import paper_2502_17599_amd as pkg
     dev = torch.device(device)
     dt = data["q"].dtype
+    if wl.n_score_rows == wl.seq_len and wl.seq_len != wl.window:
+        flags |= pkg.FLAG_FULL_PROMPT       # the workload carries a query for every prompt position
     params = pkg.make_params(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.seq_len, wl.window,
                              wl.total_budget, dt, wl.recent_num, wl.recent_den, 0.0, flags)
     comp = pkg.Compressor(params, dev, want_merge_assign=True)
