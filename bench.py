@@ -31,14 +31,16 @@ PHASE_BOUND = {"score_stats": "hbm", "score_accum": "hbm", "similarity": "mfma",
 
 
 def algorithmic_work(wl, budgets):
-    """Per launch: bytes the method itself must move (hbm phases) or flops it must do (similarity)."""
+    """Per launch: bytes the method itself must move (hbm phases) or flops it must do (similarity; the
+    scoring when every prompt row scores: the logits of the causal triangle once)."""
     L, Hkv, T, d = wl.n_layers, wl.n_kv_heads, wl.seq_len, wl.head_dim
     e = 2 if wl.dtype == "bf16" else 4
     k_bytes = L * Hkv * T * d * e
     out_rows = int(sum(budgets)) * Hkv
     less = [(T - s) * Hkv for s in budgets]
+    full_prompt = wl.n_score_rows == T and T != wl.window
     return {
-        "score_stats": k_bytes,                                    # every key once
+        "score_stats": (1.0 * L * wl.n_q_heads * T * (T + 1) * d) if full_prompt else k_bytes,   # flops / every key once
         "score_accum": k_bytes,                                    # every key once
         "similarity": sum(2.0 * (T - s) * s * d * Hkv for s in budgets),   # flops
         "merge_write": 2 * k_bytes + 2 * out_rows * d * e,         # every K and V row once + the output
@@ -139,6 +141,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llava7b_multi_image")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--full-prompt", action="store_true",
+                    help="score with every prompt position instead of the observation window")
     ap.add_argument("--no-decode", action="store_true", help="skip the decoding-step measurement")
     ap.add_argument("--no-phase-events", action="store_true",
                     help="do not record per-kernel HIP events inside the timed region")
@@ -166,11 +170,18 @@ def main():
     from workloads import generate, get_workload
 
     wl = get_workload(args.workload)
+    flags = 0
+    if args.full_prompt:       # every prompt position scores the keys (the three scoring kernels are timed as one)
+        from workloads import variant
+        wl = variant(wl, score_rows=wl.seq_len)
+        flags = pkg.FLAG_FULL_PROMPT
+        PHASE_BOUND["score_stats"] = "mfma"
+        PHASE_KERNELS["score_stats"] = ["score_stats_kernel", "stats_combine_kernel", "score_accum_kernel"]
     dev = torch.device("cuda:0")
     data = generate(wl, threads=16)
     q, k, v, mask = (data[n].to(dev) for n in ("q", "k", "v", "mask"))
     params = pkg.make_params(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.seq_len, wl.window,
-                             wl.total_budget, q.dtype, wl.recent_num, wl.recent_den)
+                             wl.total_budget, q.dtype, wl.recent_num, wl.recent_den, 0.0, flags)
     comp = pkg.Compressor(params, dev, want_entropy=True, want_sel_idx=True, want_merge_assign=False)
     stream = torch.cuda.current_stream(dev)
 
@@ -212,7 +223,8 @@ def main():
         else:
             achieved, peak, unit = work[dom] / t_s / 1e9, HBM_PEAK_GBS, "GB/s"
         roofline = {"kernel": dom, "launches": PHASE_KERNELS[dom], "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                    "frac": achieved / peak, "traffic": measured_traffic(wl.name, dom),
+                    "frac": achieved / peak,
+                    "traffic": None if args.full_prompt else measured_traffic(wl.name, dom),
                     "kernel_ms": dom_ms, "launches_timed": n_calls}
 
     e = 2 if wl.dtype == "bf16" else 4
@@ -222,7 +234,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
         "data": "synthetic",
-        "config": {"workload": wl.name, "layers": wl.n_layers, "q_heads": wl.n_q_heads, "kv_heads": wl.n_kv_heads,
+        "config": {"workload": wl.name + ("+full_prompt_scoring" if args.full_prompt else ""), "layers": wl.n_layers, "q_heads": wl.n_q_heads, "kv_heads": wl.n_kv_heads,
                    "head_dim": wl.head_dim, "seq_len": wl.seq_len, "window": wl.window,
                    "total_budget": wl.total_budget, "seed": wl.seed},
         "kv_rows_per_sec": wl.n_layers * wl.n_kv_heads * wl.seq_len / (ms_per_step * 1e-3),
