@@ -1,0 +1,59 @@
+"""Seeded sweep over small shapes (sequence length, window, group size, head dimension, storage type, layout,
+budget, recent share) through the whole pass and one decoding step, against the oracles."""
+import numpy as np
+import pytest
+
+from workloads import generate, get_workload, variant
+
+from parity import check_all, run_gpu
+
+pytestmark = pytest.mark.gpu
+TINY = get_workload("tiny")
+
+
+def _random_layout(r, T):
+    """Alternating text / vision segments of random lengths that sum to T; ends with text or vision at random."""
+    segs, left, kind, grp = [], T, ("t" if r.random() < 0.5 else "v"), 0
+    while left > 0:
+        n = int(min(left, r.integers(1, max(2, T // 3))))
+        if kind == "v":
+            segs.append(("v", n, grp)); grp += 1
+        else:
+            segs.append(("t", n, -1))
+        left -= n
+        kind = "v" if kind == "t" else "t"
+    return tuple(segs)
+
+
+def _configs():
+    r = np.random.Generator(np.random.Philox(key=[2024, 5]))
+    out = []
+    for i in range(14):
+        T = int(r.choice([40, 63, 64, 65, 127, 129, 200, 257, 300, 511, 640]))
+        W = int(min(T, r.choice([1, 2, 7, 31, 32, 33, 64, 100, 128])))
+        hkv = int(r.choice([1, 2, 3]))
+        G = int(r.choice([1, 2, 3, 4, 5, 8]))
+        while G * ((W + 31) // 32) > 32:
+            G //= 2
+        d = int(r.choice([64, 128]))
+        dtype = str(r.choice(["f32", "bf16"]))
+        L = int(r.integers(1, 5))
+        lo, hi = L * W, L * T
+        B = int(r.integers(lo, hi + 1)) if r.random() < 0.8 else int(r.choice([lo, hi]))
+        num, den = [(3, 4), (0, 1), (1, 1), (1, 2)][int(r.integers(0, 4))]
+        out.append(variant(TINY, name=f"rand{i}", n_layers=L, n_q_heads=hkv * G, n_kv_heads=hkv, head_dim=d, dtype=dtype,
+                           layout=_random_layout(r, T), window=W, total_budget=B, seed=100 + i, recent_num=num,
+                           recent_den=den, tau_lo=0.3, tau_hi=3.0, heavy_frac=float(r.choice([0.0, 0.02, 0.1]))))
+    return out
+
+
+@pytest.mark.parametrize("wl", _configs(), ids=lambda w: w.name)
+def test_random_shape(wl):
+    print(f"\n[random case] {wl.name}: L={wl.n_layers} Hq={wl.n_q_heads} Hkv={wl.n_kv_heads} d={wl.head_dim} T={wl.seq_len} "
+          f"W={wl.window} B={wl.total_budget} {wl.dtype} recent={wl.recent_num}/{wl.recent_den} layout={wl.layout}", flush=True)
+    data = generate(wl)
+    comp, gpu = run_gpu(wl, data)
+    check_all(wl, data, gpu)
+    # one decoding step over the cache this shape produces, with a few appended rows
+    from test_gpu_decode import _check as check_decode
+    check_decode(wl, n_new=wl.seed % 4)
