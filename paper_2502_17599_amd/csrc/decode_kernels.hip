@@ -83,31 +83,44 @@ struct Elems<float> {
   static __device__ __forceinline__ void store(char* dst, float x) { *reinterpret_cast<float*>(dst) = x; }
 };
 
+// Value of a partner lane whose lane-index bit X differs (X = 1, 2, 4, 8 inside a row of 16 lanes: data-parallel
+// primitives, no LDS traffic; the partners of 4 and 8 are the mirrored lanes of the half row / row, which differ
+// in the lower bits too; X = 16: the lane 16 away).
+template <int X>
+__device__ __forceinline__ float lane_partner(float v) {
+  const int i = __float_as_int(v);
+  if constexpr (X == 1) return __int_as_float(__builtin_amdgcn_update_dpp(i, i, 0xB1, 0xF, 0xF, true));        // quad_perm 1,0,3,2
+  else if constexpr (X == 2) return __int_as_float(__builtin_amdgcn_update_dpp(i, i, 0x4E, 0xF, 0xF, true));   // quad_perm 2,3,0,1
+  else if constexpr (X == 4) return __int_as_float(__builtin_amdgcn_update_dpp(i, i, 0x141, 0xF, 0xF, true));  // row_half_mirror
+  else if constexpr (X == 8) return __int_as_float(__builtin_amdgcn_update_dpp(i, i, 0x140, 0xF, 0xF, true));  // row_mirror
+  else return __shfl_xor(v, X, kWave);
+}
+
 // The LPR lanes that read one row each hold, for every query head of the group, a partial dot product.
-// row_reduce_scatter sums them over the lanes and leaves in v[0] the total of ONE head per lane (the
-// head row_head() names: the upper lane-index bits choose it), at GP + log2(LPR) - 1 exchanges instead
-// of GP * log2(LPR); row_all_gather is the inverse: from one value per lane for that lane's head to all
-// GP values in every lane.
-template <int GP, int LPR>
-__device__ __forceinline__ void row_reduce_scatter(float (&v)[GP], int cc) {
-  int n = GP;
+// RowReduceScatter sums them over the lanes and leaves in v[0] the total of ONE head per lane (the head
+// row_head() names: the upper lane-index bits choose it), at GP + log2(LPR) - 1 exchanges instead of
+// GP * log2(LPR); RowAllGather is the inverse: from one value per lane for that lane's head to all GP
+// values in every lane.  N: values still held, X: bit in which the partner differs.  All array indices
+// are compile-time constants (the arrays live in registers).
+template <int GP, int N, int X>
+struct RowReduceScatter {
+  static __device__ __forceinline__ void run(float (&v)[GP], int cc) {
+    if constexpr (X >= 1) {
+      if constexpr (N > 1) {
+        const bool up = (cc & X) != 0;
 #pragma unroll
-  for (int x = LPR / 2; x >= 1; x >>= 1) {
-    if (n > 1) {
-      const bool up = (cc & x) != 0;
-      n >>= 1;
-#pragma unroll
-      for (int i = 0; i < GP / 2; ++i) {
-        if (i < n) {
-          const float keep = up ? v[i + n] : v[i], send = up ? v[i] : v[i + n];
-          v[i] = keep + __shfl_xor(send, x, kWave);
+        for (int i = 0; i < N / 2; ++i) {
+          const float keep = up ? v[i + N / 2] : v[i], send = up ? v[i] : v[i + N / 2];
+          v[i] = keep + lane_partner<X>(send);
         }
+        RowReduceScatter<GP, N / 2, X / 2>::run(v, cc);
+      } else {
+        v[0] += lane_partner<X>(v[0]);
+        RowReduceScatter<GP, 1, X / 2>::run(v, cc);
       }
-    } else {
-      v[0] += __shfl_xor(v[0], x, kWave);
     }
   }
-}
+};
 template <int GP, int LPR>
 __device__ __forceinline__ int row_head(int cc) {
   int h = 0, n = GP;
@@ -120,25 +133,31 @@ __device__ __forceinline__ int row_head(int cc) {
   }
   return h;
 }
+// N: values held so far (w[0..N)), X: partner bit of this step; the steps run from the last halving
+// distance of the reduce-scatter back up to LPR / 2.
+template <int GP, int N, int X>
+struct RowAllGather {
+  static __device__ __forceinline__ void run(float (&w)[GP], int cc) {
+    if constexpr (N < GP) {
+      const bool up = (cc & X) != 0;
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        const float other = lane_partner<X>(w[i]);
+        w[i + N] = up ? w[i] : other;
+        w[i] = up ? other : w[i];
+      }
+      RowAllGather<GP, 2 * N, 2 * X>::run(w, cc);
+    }
+  }
+};
+template <int GP, int LPR>
+__device__ __forceinline__ void row_reduce_scatter(float (&v)[GP], int cc) {
+  RowReduceScatter<GP, GP, LPR / 2>::run(v, cc);
+}
 template <int GP, int LPR>
 __device__ __forceinline__ void row_all_gather(float mine, float (&w)[GP], int cc) {
   w[0] = mine;
-  constexpr int kSteps = GP == 1 ? 0 : (GP == 2 ? 1 : (GP == 4 ? 2 : 3));
-  int n = 1;
-#pragma unroll
-  for (int st = kSteps - 1; st >= 0; --st) {
-    const int x = (LPR / 2) >> st;  // the exchange distances of the halving steps, last one first
-    const bool up = (cc & x) != 0;
-#pragma unroll
-    for (int i = 0; i < GP / 2; ++i) {
-      if (i < n) {
-        const float other = __shfl_xor(w[i], x, kWave);
-        w[i + n] = up ? w[i] : other;
-        w[i] = up ? other : w[i];
-      }
-    }
-    n <<= 1;
-  }
+  RowAllGather<GP, 1, LPR / GP>::run(w, cc);   // the last halving step of the reduce-scatter had distance LPR / GP
 }
 
 // grid (NP, Hkv, L), 256 threads.  A row is read by LPR = row bytes / 16 lanes (16 bytes each), so a
