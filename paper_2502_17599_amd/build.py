@@ -14,6 +14,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # keep the compiler from forming packed-fp32 instructions out of ordinary float code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # matrix products accumulate in ordinary vector registers: the scoring kernels read every accumulator
+    # element with vector instructions, which would cost one extra move per element out of the accumulator file
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-Wno-unused-command-line-argument",
 ]
 

@@ -9,6 +9,8 @@
 //                                scores A_s and into the head-averaged cross-modal matrix, whose row
 //                                entropies are reduced per tile
 // Logits are kept in the base-2 domain: t = (q.k) * scale * log2(e), probabilities are exp2(t - max).
+#include <type_traits>
+
 #include "device_utils.hpp"
 #include "plan.hpp"
 
@@ -211,13 +213,21 @@ __global__ void __launch_bounds__(256) stats_combine_kernel(ScoreArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------ pass B
-// grid (NT, L); 4 waves; wave w owns the 32 key columns w*32.. of the tile, a lane owns one column.
+// grid (NT, L); NW = 4 or 8 waves.  Wave (cw, rh) = (wave & 3, wave >> 2) owns the 32 key columns cw*32.. of
+// the tile (a lane owns one column) and the row blocks rh*RBW .. rh*RBW + RBW-1 of the window, RBW = RB / (NW/4).
 // The workgroup walks over all kv heads and, inside, the query heads of the group, so the
 // head-averaged cross-modal probabilities of its W x 128 patch accumulate in registers (same
 // accumulator layout for every head) and the entropy terms p log p can be taken once at the end.
-template <typename T, int D, int RB, bool KSTAGE>
-__global__ void __launch_bounds__(256, (RB == 1 && sizeof(T) == 2 && !KSTAGE) ? 3 : 1) score_accum_kernel(ScoreArgs a) {
+// Eight waves (two per SIMD, each with half of the rows) let one wave's exponentials run beside the
+// other's matrix products; they are used when a wave would otherwise hold several row blocks.
+template <typename T, int D, int RB, bool KSTAGE, int NW>
+__global__ void __launch_bounds__(NW * 64, (NW == 8) ? 2 : ((RB == 1 && sizeof(T) == 2 && !KSTAGE) ? 3 : 1))
+    score_accum_kernel(ScoreArgs a) {
   using TL = Tile<T, D>;
+  constexpr int NTHR = NW * 64;
+  constexpr int NRH = NW / 4;     // row groups of the workgroup
+  constexpr int RBW = RB / NRH;   // row blocks per wave
+  static_assert(RB % NRH == 0, "row blocks must split evenly over the row groups");
   extern __shared__ __align__(16) char smem[];
   char* ktile = smem;
   char* qtile = ktile + kScoreTile * TL::kStride;
@@ -225,14 +235,16 @@ __global__ void __launch_bounds__(256, (RB == 1 && sizeof(T) == 2 && !KSTAGE) ? 
   float* st_rz = st_m + RB * 32;
   float* st_cv = st_rz + RB * 32;
   float* st_ct = st_cv + RB * 32;
-  double* red = reinterpret_cast<double*>(st_ct + RB * 32);  // [4][2]
+  float* colred = st_ct + RB * 32;                                  // [kScoreTile] column sums of the second row group
+  double* red = reinterpret_cast<double*>(colred + kScoreTile);     // [NW][2]
 
   // layers are walked in the opposite order of pass A, so the keys pass A touched last (still in the
   // memory-side cache) are the first ones read here
   const int tile = blockIdx.x, l = a.L - 1 - blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, kg = lane >> 5;
+  const int cw = wave & 3, rh = wave >> 2;
   const int j0 = tile * kScoreTile;
-  const int j = j0 + wave * 32 + n;  // this lane's key column
+  const int j = j0 + cw * 32 + n;  // this lane's key column
   const bool col_ok = j < a.T;
   const bool col_is_vision = col_ok && a.mask[j] != 0;
   const float* st_coef = col_is_vision ? st_cv : st_ct;
@@ -240,9 +252,9 @@ __global__ void __launch_bounds__(256, (RB == 1 && sizeof(T) == 2 && !KSTAGE) ? 
   const int rows_valid = min(kScoreTile, a.T - j0);
   const int Wp = RB * 32;
 
-  float pbar[RB][16];
+  float pbar[RBW][16];
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
+  for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) pbar[rb][r] = 0.f;
 
@@ -250,30 +262,42 @@ __global__ void __launch_bounds__(256, (RB == 1 && sizeof(T) == 2 && !KSTAGE) ? 
   // into registers while head h is processed out of LDS.  With grouped heads (KSTAGE false) the key
   // tile changes only every G heads: it is then loaded on the spot, which keeps 32 registers free
   // (two waves per SIMD instead of one) at the price of one exposed load per group.
-  TileStage<T, D, KSTAGE ? kScoreTile : 1> kstage;
-  TileStage<T, D, RB * 32> qstage;
+  TileStage<T, D, KSTAGE ? kScoreTile : 1, NTHR> kstage;
+  TileStage<T, D, RB * 32, NTHR> qstage;
   float4 sreg = make_float4(0.f, 0.f, 0.f, 0.f);
   const char* ktile_src = a.k + ((size_t)l * a.Hkv * a.Tk + j0) * TL::kRowBytes;
   const size_t khead_stride = (size_t)a.Tk * TL::kRowBytes;
-  if (KSTAGE) kstage.template fetch<true>(ktile_src, rows_valid, tid, 256);
-  qstage.fetch(a.q + ((size_t)(l * a.Hq) * a.q_rows + a.q_row0) * TL::kRowBytes, a.W, tid, 256);
+  if (KSTAGE) kstage.template fetch<true>(ktile_src, rows_valid, tid, NTHR);
+  qstage.fetch(a.q + ((size_t)(l * a.Hq) * a.q_rows + a.q_row0) * TL::kRowBytes, a.W, tid, NTHR);
   if (tid < Wp) sreg = a.stats[(size_t)(l * a.Hq) * a.Wp + tid];
 
   Frag<T, D> kf;
   float colsum = 0.f;
+  float pending = 0.f;   // column sum of a finished kv head, waiting for the other row group's share
+  int pending_g = -1;
+  // Adds the second row group's share (left in colred before the last barrier) and writes the column score.
+  auto flush_pending = [&]() {
+    if (NRH > 1 && pending_g >= 0 && rh == 0 && kg == 0 && col_ok) {
+      const float tot = pending + colred[cw * 32 + n];
+      float* dst = a.col_scores + (size_t)(l * a.Hkv + pending_g) * a.Tk + j;
+      *dst = a.accumulate ? *dst + tot : tot;  // one writer per column and launch
+    }
+    pending_g = -1;
+  };
   for (int h = 0; h < a.Hq; ++h) {
     const int g = h / a.G, hg = h - g * a.G;
     __syncthreads();  // the previous head's tiles are no longer read
+    if (NRH > 1) flush_pending();
     if (hg == 0) {
       if (KSTAGE) {
-        kstage.commit(ktile, tid, 256);
+        kstage.commit(ktile, tid, NTHR);
       } else {
-        TileStage<T, D, kScoreTile> now;
-        now.template fetch<true>(ktile_src + (size_t)g * khead_stride, rows_valid, tid, 256);
-        now.commit(ktile, tid, 256);
+        TileStage<T, D, kScoreTile, NTHR> now;
+        now.template fetch<true>(ktile_src + (size_t)g * khead_stride, rows_valid, tid, NTHR);
+        now.commit(ktile, tid, NTHR);
       }
     }
-    qstage.commit(qtile, tid, 256);
+    qstage.commit(qtile, tid, NTHR);
     if (tid < Wp) {
       st_m[tid] = sreg.x;
       st_rz[tid] = sreg.y;
@@ -283,48 +307,71 @@ __global__ void __launch_bounds__(256, (RB == 1 && sizeof(T) == 2 && !KSTAGE) ? 
     __syncthreads();
     if (h + 1 < a.Hq) {
       const int hn = h + 1;
-      if (KSTAGE && hn % a.G == 0) kstage.template fetch<true>(ktile_src + (size_t)(hn / a.G) * khead_stride, rows_valid, tid, 256);
-      qstage.fetch(a.q + ((size_t)(l * a.Hq + hn) * a.q_rows + a.q_row0) * TL::kRowBytes, a.W, tid, 256);
+      if (KSTAGE && hn % a.G == 0) kstage.template fetch<true>(ktile_src + (size_t)(hn / a.G) * khead_stride, rows_valid, tid, NTHR);
+      qstage.fetch(a.q + ((size_t)(l * a.Hq + hn) * a.q_rows + a.q_row0) * TL::kRowBytes, a.W, tid, NTHR);
       if (tid < Wp) sreg = a.stats[(size_t)(l * a.Hq + hn) * a.Wp + tid];
     }
     if (hg == 0) {
-      frag_load(kf, ktile + (wave * 32 + n) * TL::kStride, kg);
+      frag_load(kf, ktile + (cw * 32 + n) * TL::kStride, kg);
       colsum = 0.f;
     }
+    // One query head against the wave's key columns.  MASKED: the tile touches the causal diagonal or the end
+    // of the sequence, so every probability is checked against its row; all other tiles take the plain path.
+    auto head_block = [&](auto masked_tag) {
+      constexpr bool MASKED = decltype(masked_tag)::value;
+      // Row r (without the lane group's offset kg*4) counts for this lane's column iff row_min <= r < row_end:
+      // the row exists (r + kg*4 < W) and sees the column (j <= T - W + r + kg*4).  The bounds are made opaque
+      // here so that the 16 comparisons per row block are redone per head instead of being kept in registers.
+      int row_min = col_ok ? j - (a.T - a.W) - kg * 4 : (1 << 30);
+      int row_end = a.W - kg * 4;
+      if (MASKED) asm volatile("" : "+v"(row_min), "+v"(row_end));
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      Frag<T, D> qf;
-      frag_load(qf, qtile + (rb * 32 + n) * TL::kStride, kg);
-      f32x16_t acc = acc_zero();
-      mma<T, D>(acc, qf, kf);
+      for (int rbl = 0; rbl < RBW; ++rbl) {
+        const int rb = rh * RBW + rbl;
+        Frag<T, D> qf;
+        frag_load(qf, qtile + (rb * 32 + n) * TL::kStride, kg);
+        f32x16_t acc = acc_zero();
+        mma<T, D>(acc, qf, kf);
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int row0 = rb * 32 + r4 * 8 + kg * 4;  // rows of acc[r4*4 .. r4*4+3]
-        const float4 m4 = *reinterpret_cast<const float4*>(st_m + row0);
-        const float4 z4 = *reinterpret_cast<const float4*>(st_rz + row0);
-        const float4 c4 = *reinterpret_cast<const float4*>(st_coef + row0);
-        const float mm[4] = {m4.x, m4.y, m4.z, m4.w};
-        const float zz[4] = {z4.x, z4.y, z4.z, z4.w};
-        const float cc[4] = {c4.x, c4.y, c4.z, c4.w};
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int row0 = rb * 32 + r4 * 8 + kg * 4;  // rows of acc[r4*4 .. r4*4+3]
+          const float4 m4 = *reinterpret_cast<const float4*>(st_m + row0);
+          const float4 z4 = *reinterpret_cast<const float4*>(st_rz + row0);
+          const float4 c4 = *reinterpret_cast<const float4*>(st_coef + row0);
+          const float mm[4] = {m4.x, m4.y, m4.z, m4.w};
+          const float zz[4] = {z4.x, z4.y, z4.z, z4.w};
+          const float cc[4] = {c4.x, c4.y, c4.z, c4.w};
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float e = fast_exp2(fmaf(acc[r4 * 4 + i], a.c, -mm[i]));
-          if (!full) {
-            const int row = row0 + i;
-            e = (col_ok && row < a.W && j <= a.T - a.W + row) ? e : 0.f;
+          for (int i = 0; i < 4; ++i) {
+            float e = fast_exp2(fmaf(acc[r4 * 4 + i], a.c, -mm[i]));
+            if (MASKED) e = (rb * 32 + r4 * 8 + i >= row_min && rb * 32 + r4 * 8 + i < row_end) ? e : 0.f;
+            colsum = fmaf(e, zz[i], colsum);
+            pbar[rbl][r4 * 4 + i] = fmaf(e, cc[i], pbar[rbl][r4 * 4 + i]);
           }
-          colsum = fmaf(e, zz[i], colsum);
-          pbar[rb][r4 * 4 + i] = fmaf(e, cc[i], pbar[rb][r4 * 4 + i]);
         }
       }
-    }
+    };
+    if (full)
+      head_block(std::false_type{});
+    else
+      head_block(std::true_type{});
     if (hg == a.G - 1) {
       const float tot = colsum + __shfl_xor(colsum, 32, kWave);
-      if (kg == 0 && col_ok) {
-        float* dst = a.col_scores + (size_t)(l * a.Hkv + g) * a.Tk + j;
-        *dst = a.accumulate ? *dst + tot : tot;  // one writer per column and launch
+      if (NRH == 1) {
+        if (kg == 0 && col_ok) {
+          float* dst = a.col_scores + (size_t)(l * a.Hkv + g) * a.Tk + j;
+          *dst = a.accumulate ? *dst + tot : tot;  // one writer per column and launch
+        }
+      } else {
+        if (rh == 1 && kg == 0) colred[cw * 32 + n] = tot;  // read after the next barrier
+        pending = tot;
+        pending_g = g;
       }
     }
+  }
+  if (NRH > 1) {
+    __syncthreads();
+    flush_pending();
   }
 
   // entropy terms of the head-averaged cross-modal probabilities.  A vision column only receives
@@ -332,7 +379,7 @@ __global__ void __launch_bounds__(256, (RB == 1 && sizeof(T) == 2 && !KSTAGE) ? 
   const float inv_heads = 1.0f / (float)a.Hq;
   float s = 0.f;
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
+  for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const float p = pbar[rb][r] * inv_heads;
@@ -340,14 +387,15 @@ __global__ void __launch_bounds__(256, (RB == 1 && sizeof(T) == 2 && !KSTAGE) ? 
     }
   const double tv = wave_sum(col_is_vision ? (double)s : 0.0);
   const double vt = wave_sum((col_ok && !col_is_vision) ? (double)s : 0.0);
-  __syncthreads();
   if (lane == 0) {
     red[wave * 2 + 0] = tv;
     red[wave * 2 + 1] = vt;
   }
   __syncthreads();
   if (tid < 2) {
-    const double sum = red[tid] + red[2 + tid] + red[4 + tid] + red[6 + tid];
+    double sum = 0.0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) sum += red[w * 2 + tid];
     double* dst = a.ent_part + ((size_t)l * a.NTk + tile) * 2 + tid;
     *dst = a.accumulate ? *dst - sum : -sum;
   }
@@ -413,16 +461,17 @@ hipError_t launch_stats_combine(const Plan& p, const Buffers& b, hipStream_t s) 
   return hipGetLastError();
 }
 
-template <typename T, int D, int RB, bool KSTAGE>
+template <typename T, int D, int RB, bool KSTAGE, int NW>
 static hipError_t launch_accum_k(const Plan& p, const ScoreArgs& a, hipStream_t s) {
-  const size_t lds = (size_t)(kScoreTile + RB * 32) * Tile<T, D>::kStride + 4 * RB * 32 * sizeof(float) + 64;
-  auto kern = score_accum_kernel<T, D, RB, KSTAGE>;
+  const size_t lds = (size_t)(kScoreTile + RB * 32) * Tile<T, D>::kStride + (4 * RB * 32 + kScoreTile) * sizeof(float) +
+                     NW * 2 * sizeof(double);
+  auto kern = score_accum_kernel<T, D, RB, KSTAGE, NW>;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(kern, dim3(p.NT, p.L), dim3(256), lds, s, a);
+  hipLaunchKernelGGL(kern, dim3(p.NT, p.L), dim3(NW * 64), lds, s, a);
   return hipGetLastError();
 }
 
@@ -431,8 +480,9 @@ static hipError_t launch_accum_t(const Plan& p, const ScoreArgs& a, hipStream_t 
   // Staging the next head's key tile through registers pays when every head brings a new key tile
   // (G == 1), except for the smallest shape, where the registers buy a third workgroup per CU instead.
   constexpr bool kThreeGroups = RB == 1 && sizeof(T) == 2;
-  if (p.G == 1 && !kThreeGroups) return launch_accum_k<T, D, RB, true>(p, a, s);
-  return launch_accum_k<T, D, RB, false>(p, a, s);
+  constexpr int NW = RB == 4 ? 8 : 4;  // four row blocks: two row groups of two (measured: no gain for two row blocks)
+  if (p.G == 1 && !kThreeGroups) return launch_accum_k<T, D, RB, true, NW>(p, a, s);
+  return launch_accum_k<T, D, RB, false, NW>(p, a, s);
 }
 
 template <typename T, int D>
