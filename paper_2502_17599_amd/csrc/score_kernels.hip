@@ -127,34 +127,51 @@ __global__ void __launch_bounds__(NW * 64, (NQ == 1 && NW == 4 && sizeof(T) == 2
         if (q < nvalid) {
           f32x16_t acc = acc_zero();
           mma<T, D>(acc, kf, qf[q]);
-          float t[16];
+          if (full) {
+            // every key of the block counts: the maximum is taken on the raw products (the scale is positive, so
+            // it commutes with the maximum) and the scale is folded into the exponent's multiply-add
+            float bm = fmaxf(fmaxf(acc[0], acc[1]), acc[2]);
 #pragma unroll
-          for (int r = 0; r < 16; ++r) t[r] = acc[r] * a.c;
-          if (!full) {
+            for (int r = 3; r < 15; r += 2) bm = fmaxf(fmaxf(bm, acc[r]), acc[r + 1]);
+            bm = fmaxf(bm, acc[15]);
+            const float mn = fmaxf(m[q], bm * a.c);
+            const float sc = fast_exp2(m[q] - mn);
+            zv[q] *= sc;
+            zt[q] *= sc;
+            m[q] = mn;
+            if (uniform) {
+              float s = 0.f;
+#pragma unroll
+              for (int r = 0; r < 16; ++r) s += fast_exp2(fmaf(acc[r], a.c, -mn));
+              if (mword)
+                zv[q] += s;
+              else
+                zt[q] += s;
+            } else {
+#pragma unroll
+              for (int r = 0; r < 16; ++r) {
+                const float e = fast_exp2(fmaf(acc[r], a.c, -mn));
+                const bool vis = (mword >> acc_row(r, kg)) & 1u;
+                zv[q] += vis ? e : 0.f;
+                zt[q] += vis ? 0.f : e;
+              }
+            }
+          } else {
+            float t[16];
             const int p = a.T - a.W + qrow[q];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
               const int j = jb + acc_row(r, kg);
-              t[r] = (j < a.T && j <= p) ? t[r] : kNegBig;
+              t[r] = (j < a.T && j <= p) ? acc[r] * a.c : kNegBig;
             }
-          }
-          float bm = t[0];
+            float bm = t[0];
 #pragma unroll
-          for (int r = 1; r < 16; ++r) bm = fmaxf(bm, t[r]);
-          const float mn = fmaxf(m[q], bm);
-          const float sc = fast_exp2(m[q] - mn);
-          zv[q] *= sc;
-          zt[q] *= sc;
-          m[q] = mn;
-          if (uniform) {
-            float s = 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s += fast_exp2(t[r] - mn);
-            if (mword)
-              zv[q] += s;
-            else
-              zt[q] += s;
-          } else {
+            for (int r = 1; r < 16; ++r) bm = fmaxf(bm, t[r]);
+            const float mn = fmaxf(m[q], bm);
+            const float sc = fast_exp2(m[q] - mn);
+            zv[q] *= sc;
+            zt[q] *= sc;
+            m[q] = mn;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
               const float e = (t[r] > 0.5f * kNegBig) ? fast_exp2(t[r] - mn) : 0.f;
