@@ -144,6 +144,9 @@ def main():
     ap.add_argument("--full-prompt", action="store_true",
                     help="score with every prompt position instead of the observation window")
     ap.add_argument("--no-decode", action="store_true", help="skip the decoding-step measurement")
+    ap.add_argument("--batch", type=int, default=0, metavar="N",
+                    help="compress N sequences of the workload's shape (different seeds) per call; the "
+                         "value is then the tokens of all N sequences per second")
     ap.add_argument("--no-phase-events", action="store_true",
                     help="do not record per-kernel HIP events inside the timed region")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
@@ -178,10 +181,15 @@ def main():
         PHASE_BOUND["score_stats"] = "mfma"
         PHASE_KERNELS["score_stats"] = ["score_stats_kernel", "stats_combine_kernel", "score_accum_kernel"]
     dev = torch.device("cuda:0")
-    data = generate(wl, threads=16)
+    n_seqs = max(args.batch, 0)
+    if n_seqs:
+        from workloads import generate_batch, variant
+        data = generate_batch([variant(wl, seed=wl.seed + i) for i in range(n_seqs)], threads=16)
+    else:
+        data = generate(wl, threads=16)
     q, k, v, mask = (data[n].to(dev) for n in ("q", "k", "v", "mask"))
     params = pkg.make_params(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.seq_len, wl.window,
-                             wl.total_budget, q.dtype, wl.recent_num, wl.recent_den, 0.0, flags)
+                             wl.total_budget, q.dtype, wl.recent_num, wl.recent_den, 0.0, flags, n_seqs)
     comp = pkg.Compressor(params, dev, want_entropy=True, want_sel_idx=True, want_merge_assign=False)
     stream = torch.cuda.current_stream(dev)
 
@@ -211,8 +219,12 @@ def main():
     dom_ms = phase_ms[names.index(dom)] / n_calls if n_calls else None
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    budgets = out.layer_len.cpu().tolist()
-    work = algorithmic_work(wl, budgets)
+    seqs = max(n_seqs, 1)
+    budgets = out.layer_len.cpu().reshape(seqs, wl.n_layers).tolist()
+    work = {}
+    for b in budgets:          # the sequences of a batch are independent: their work adds up
+        for key, val in algorithmic_work(wl, b).items():
+            work[key] = work.get(key, 0) + val
 
     roofline = None
     if dom_ms:
@@ -224,29 +236,29 @@ def main():
             achieved, peak, unit = work[dom] / t_s / 1e9, HBM_PEAK_GBS, "GB/s"
         roofline = {"kernel": dom, "launches": PHASE_KERNELS[dom], "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
                     "frac": achieved / peak,
-                    "traffic": None if args.full_prompt else measured_traffic(wl.name, dom),
+                    "traffic": None if (args.full_prompt or n_seqs) else measured_traffic(wl.name, dom),
                     "kernel_ms": dom_ms, "launches_timed": n_calls}
 
     e = 2 if wl.dtype == "bf16" else 4
     alg_bytes = work["merge_write"]        # K and V once + the output: the traffic of the whole pass
     rec = {
-        "metric": "kv_tokens_compressed_per_sec", "value": wl.seq_len / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "metric": "kv_tokens_compressed_per_sec", "value": seqs * wl.seq_len / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
         "data": "synthetic",
         "config": {"workload": wl.name + ("+full_prompt_scoring" if args.full_prompt else ""), "layers": wl.n_layers, "q_heads": wl.n_q_heads, "kv_heads": wl.n_kv_heads,
                    "head_dim": wl.head_dim, "seq_len": wl.seq_len, "window": wl.window,
-                   "total_budget": wl.total_budget, "seed": wl.seed},
-        "kv_rows_per_sec": wl.n_layers * wl.n_kv_heads * wl.seq_len / (ms_per_step * 1e-3),
+                   "total_budget": wl.total_budget, "seed": wl.seed, "batch": seqs},
+        "kv_rows_per_sec": seqs * wl.n_layers * wl.n_kv_heads * wl.seq_len / (ms_per_step * 1e-3),
         "pass_hbm_frac": (alg_bytes / (ms_per_step * 1e-3)) / (HBM_PEAK_GBS * 1e9),
-        "pass_mfma_frac": ((work["similarity"] + 2.0 * wl.n_layers * wl.n_q_heads * wl.window * wl.seq_len * wl.head_dim)
+        "pass_mfma_frac": ((work["similarity"] + 2.0 * seqs * wl.n_layers * wl.n_q_heads * wl.window * wl.seq_len * wl.head_dim)
                            / (ms_per_step * 1e-3)) / (MFMA_PEAK_TFLOPS[wl.dtype] * 1e12),
         "phase_ms_warmup": per_phase,
         "roofline": roofline,
     }
-    if not args.no_decode:
+    if not args.no_decode and not n_seqs:
         rec["decode_step"] = decode_step_record(pkg, torch, wl, out, q.dtype, k, v, dev)
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not n_seqs:
         rec["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(rec))
 

@@ -2,7 +2,7 @@
  * libmeda -- prefill-time KV-cache compression pass of MEDA (arXiv 2502.17599) for AMD MI355X
  * (gfx950).  C ABI: plain pointers and sizes, no framework types.
  *
- * One call compresses the KV cache of one sequence over all layers:
+ * One call compresses the KV cache of one sequence (or of a batch of equally shaped sequences) over all layers:
  *   1. attention of an observation window (the last W prompt positions) against every cached
  *      key: causal softmax rows, cumulative attention score per key      (Section 3.3, A_s)
  *   2. cross-modal attention entropy of every layer                       (Section 3.2, E_CM)
@@ -62,6 +62,8 @@ typedef struct {
   int32_t dtype;        /* meda_dtype of q_win, k, v, k_out, v_out                                 */
   float softmax_scale;  /* 0 -> 1/sqrt(head_dim)                                                   */
   int32_t flags;        /* MEDA_FLAG_*                                                             */
+  int32_t n_seqs;       /* N: sequences of this shape compressed by the call (0 means 1); every array
+                           gains a leading [N] dimension, see meda_compress; N * L <= 256             */
 } meda_params;
 
 /* Bytes of device scratch meda_compress needs for these parameters; 0 if they are invalid.       */
@@ -87,6 +89,14 @@ size_t meda_workspace_bytes(const meda_params* params);
  *   workspace      at least meda_workspace_bytes(params) bytes, 256-byte aligned
  *   hip_stream     hipStream_t (NULL = the default stream)
  * Calls that share a workspace must not overlap.
+ *
+ * Several sequences (n_seqs = N > 1; the paper's throughput figures are taken on batches, Table 6): the
+ * sequences are independent and share every parameter (each gets the budget B).  Inputs are stacked:
+ * q_win [N][L][Hq][W][d], k, v [N][L][Hkv][T][d], modality [N][T].  Outputs: one ragged cache for the whole
+ * batch, sequence n occupying the rows [n*B*Hkv, (n+1)*B*Hkv); layer_len [N][L]; layer_off [N][L+1] holds
+ * ABSOLUTE offsets (layer_off[n][0] = n*B, layer_off[n][L] = (n+1)*B), so the slices of sequence n can be
+ * handed to meda_decode_attention as they are; entropy [N][L]; sel_idx [N*B*Hkv]; merge_assign [N][L][Hkv][T].
+ * The result of every sequence is bit-identical to a call of its own.
  */
 meda_status meda_compress(const meda_params* params, const void* q_win, const void* k, const void* v,
                           const uint8_t* modality, void* k_out, void* v_out, int32_t* layer_len,

@@ -445,6 +445,15 @@ def meda_compress(q_win, k, v, mask, total_budget, window, dtype="f32", scale=No
             "k_out": k_out, "v_out": v_out}
 
 
+def meda_compress_batch(q_win, k, v, masks, total_budget, window, dtype="f32", scale=None,
+                        recent_num=3, recent_den=4):
+    """A batch of sequences (the paper's throughput figures are taken on batches, Table 6): the sequences are
+    independent, each is compressed on its own with the budget ``total_budget``.  Arrays carry a leading
+    dimension N (masks [N, T]); returns the list of the N results of ``meda_compress``."""
+    return [meda_compress(q_win[n], k[n], v[n], masks[n], total_budget, window, dtype, scale, recent_num, recent_den)
+            for n in range(len(masks))]
+
+
 def kv_cache_bytes(tokens: int, n_layers: int, n_heads: int, head_dim: int, elt_bytes: int) -> int:
     """Bytes of a K+V cache holding ``tokens`` positions per layer (Appendix A.2 memory formula)."""
     return tokens * 2 * n_layers * n_heads * head_dim * elt_bytes

@@ -32,7 +32,8 @@ class MedaParams(ctypes.Structure):
     _fields_ = [("n_layers", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("seq_len", ctypes.c_int32), ("window", ctypes.c_int32),
                 ("total_budget", ctypes.c_int64), ("recent_num", ctypes.c_int32), ("recent_den", ctypes.c_int32),
-                ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("flags", ctypes.c_int32)]
+                ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("flags", ctypes.c_int32),
+                ("n_seqs", ctypes.c_int32)]
 
 
 class MedaDecodeParams(ctypes.Structure):
@@ -98,10 +99,12 @@ def _check(status: int) -> None:
 
 
 def make_params(n_layers, n_q_heads, n_kv_heads, head_dim, seq_len, window, total_budget, dtype,
-                recent_num=3, recent_den=4, softmax_scale=0.0, flags=0) -> MedaParams:
+                recent_num=3, recent_den=4, softmax_scale=0.0, flags=0, n_seqs=0) -> MedaParams:
+    """``n_seqs`` = 0: one sequence, arrays without a batch dimension; N >= 1: a batch, every array has a
+    leading dimension N (``total_budget`` is the budget of each sequence)."""
     code = _DTYPES.get(dtype, dtype if isinstance(dtype, int) else -1)
     return MedaParams(n_layers, n_q_heads, n_kv_heads, head_dim, seq_len, window, total_budget,
-                      recent_num, recent_den, code, softmax_scale, flags)
+                      recent_num, recent_den, code, softmax_scale, flags, n_seqs)
 
 
 def meda_workspace_bytes(params: MedaParams) -> int:
@@ -146,6 +149,15 @@ class CompressedCache:
     merge_assign: Optional[torch.Tensor]
     n_kv_heads: int
 
+    def sequence(self, n: int) -> "CompressedCache":
+        """Sequence n of a batched call: the same ragged buffers with that sequence's lengths and (absolute)
+        offsets, so ``layer`` and ``meda_decode_attention`` work on it as on the result of a single call."""
+        if self.layer_len.dim() != 2:
+            raise ValueError("not a batched result")
+        return CompressedCache(self.k_out, self.v_out, self.layer_len[n], self.layer_off[n],
+                               None if self.entropy is None else self.entropy[n], self.sel_idx,
+                               None if self.merge_assign is None else self.merge_assign[n], self.n_kv_heads)
+
     def layer(self, l: int):
         """(K, V[, positions]) of layer l as [Hkv, S_l, d] views."""
         off = int(self.layer_off[l]); s = int(self.layer_len[l]); h = self.n_kv_heads
@@ -175,15 +187,17 @@ class Compressor:
         dt = {0: torch.float32, 1: torch.bfloat16}[p.dtype]
         dev = self.device
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-        rows = p.total_budget * p.n_kv_heads
+        self.batch = (p.n_seqs,) if p.n_seqs >= 1 else ()   # leading dimension of every array
+        rows = max(1, p.n_seqs) * p.total_budget * p.n_kv_heads
         self.k_out = torch.empty((rows, p.head_dim), dtype=dt, device=dev)
         self.v_out = torch.empty((rows, p.head_dim), dtype=dt, device=dev)
-        self.layer_len = torch.empty(p.n_layers, dtype=torch.int32, device=dev)
-        self.layer_off = torch.empty(p.n_layers + 1, dtype=torch.int64, device=dev)
-        self.entropy = torch.empty(p.n_layers, dtype=torch.float64, device=dev) if want_entropy else None
+        self.layer_len = torch.empty(self.batch + (p.n_layers,), dtype=torch.int32, device=dev)
+        self.layer_off = torch.empty(self.batch + (p.n_layers + 1,), dtype=torch.int64, device=dev)
+        self.entropy = (torch.empty(self.batch + (p.n_layers,), dtype=torch.float64, device=dev)
+                        if want_entropy else None)
         self.sel_idx = torch.empty(rows, dtype=torch.int32, device=dev) if want_sel_idx else None
-        self.merge_assign = (torch.empty((p.n_layers, p.n_kv_heads, p.seq_len), dtype=torch.int32, device=dev)
-                             if want_merge_assign else None)
+        self.merge_assign = (torch.empty(self.batch + (p.n_layers, p.n_kv_heads, p.seq_len), dtype=torch.int32,
+                                         device=dev) if want_merge_assign else None)
 
     def region(self, name: str, dtype: torch.dtype) -> torch.Tensor:
         off, size = meda_workspace_region(self.params, name)
@@ -194,13 +208,15 @@ class Compressor:
         p = self.params
         dt = {0: torch.float32, 1: torch.bfloat16}[p.dtype]
         q_rows = p.seq_len if (p.flags & FLAG_FULL_PROMPT) else p.window
-        for name, t, shape in (("q_win", q_win, (p.n_layers, p.n_q_heads, q_rows, p.head_dim)),
-                               ("k", k, (p.n_layers, p.n_kv_heads, p.seq_len, p.head_dim)),
-                               ("v", v, (p.n_layers, p.n_kv_heads, p.seq_len, p.head_dim))):
+        nb = self.batch
+        for name, t, shape in (("q_win", q_win, nb + (p.n_layers, p.n_q_heads, q_rows, p.head_dim)),
+                               ("k", k, nb + (p.n_layers, p.n_kv_heads, p.seq_len, p.head_dim)),
+                               ("v", v, nb + (p.n_layers, p.n_kv_heads, p.seq_len, p.head_dim))):
             if tuple(t.shape) != shape or t.dtype != dt or not t.is_contiguous() or t.device != self.device:
                 raise ValueError(f"{name}: expected contiguous {dt} tensor of shape {shape} on {self.device}")
-        if tuple(modality.shape) != (p.seq_len,) or modality.dtype != torch.uint8 or modality.device != self.device:
-            raise ValueError("modality: expected uint8 tensor of shape (seq_len,) on the same device")
+        if (tuple(modality.shape) != nb + (p.seq_len,) or modality.dtype != torch.uint8
+                or modality.device != self.device or not modality.is_contiguous()):
+            raise ValueError(f"modality: expected contiguous uint8 tensor of shape {nb + (p.seq_len,)} on the same device")
         s = stream if stream is not None else torch.cuda.current_stream(self.device)
         st = self.lib.meda_compress(ctypes.byref(p), _ptr(q_win), _ptr(k), _ptr(v), _ptr(modality),
                                     _ptr(self.k_out), _ptr(self.v_out), _ptr(self.layer_len), _ptr(self.layer_off),
@@ -213,11 +229,15 @@ class Compressor:
 
 def meda_compress(q_win, k, v, modality, total_budget, recent_num=3, recent_den=4, softmax_scale=0.0,
                   flags=0, want_merge_assign=False, stream=None) -> CompressedCache:
-    """One-shot call: allocates workspace and outputs with torch, then runs the pass on the GPU."""
-    L, Hq, W, d = q_win.shape
-    _, Hkv, T, _ = k.shape
+    """One-shot call: allocates workspace and outputs with torch, then runs the pass on the GPU.  Arrays with a
+    leading batch dimension (q_win of rank 5) are compressed as a batch of sequences, each with ``total_budget``."""
+    n_seqs = q_win.shape[0] if q_win.dim() == 5 else 0
+    L, Hq, W, d = q_win.shape[-4:]
+    Hkv, T = k.shape[-3], k.shape[-2]
+    if flags & FLAG_FULL_PROMPT:
+        raise ValueError("with FLAG_FULL_PROMPT the window cannot be read off q_win: use make_params and Compressor")
     params = make_params(L, Hq, Hkv, d, T, W, int(total_budget), q_win.dtype, recent_num, recent_den,
-                         softmax_scale, flags)
+                         softmax_scale, flags, n_seqs)
     comp = Compressor(params, q_win.device, want_merge_assign=want_merge_assign)
     return comp(q_win, k, v, modality, stream)
 

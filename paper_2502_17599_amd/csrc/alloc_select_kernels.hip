@@ -15,13 +15,14 @@ struct AllocArgs {
   int32_t* layer_len;      // user outputs
   int64_t* layer_off;
   double* entropy;         // may be null
-  int L, NT, T, W, R, num, den, flags;   // W: recent window; R: scoring rows (the last R positions)
+  int L, NT, T, W, R, num, den, flags;   // L layers and budget B of ONE sequence; W: recent window; R: scoring rows
+  int N;                                 // sequences (one workgroup each)
   long long B;
 };
 
 __device__ __forceinline__ double clampd(double v, double lo, double hi) { return fmin(fmax(v, lo), hi); }
 
-// One workgroup.  S_l = B * softmax_l(E_CM) when no bound is active; shares are kept inside
+// One workgroup per sequence.  S_l = B * softmax_l(E_CM) when no bound is active; shares are kept inside
 // [min(W,T), T] by water-filling (x_l = clamp(lambda * w_l), sum x_l = B) and rounded by largest
 // remainder, so that sum_l S_l = B exactly.  All real arithmetic is double precision.
 __global__ void __launch_bounds__(256) allocate_kernel(AllocArgs a) {
@@ -31,6 +32,11 @@ __global__ void __launch_bounds__(256) allocate_kernel(AllocArgs a) {
   __shared__ double s_lambda;
   const int tid = threadIdx.x, L = a.L;
   const double lo = (double)min(a.W, a.T), hi = (double)a.T, B = (double)a.B;
+  // sequence n: its layers are the layers n*L .. n*L + L-1 of the batch, its output rows start at n*B
+  const int n = blockIdx.x;
+  a.ent_part += (size_t)n * L * a.NT * 2;
+  a.mask += (size_t)n * a.T;
+  if (a.entropy) a.entropy += (size_t)n * L;
 
   // scoring rows of each modality (the denominators of the two entropy means)
   int n_vis = 0;
@@ -128,22 +134,24 @@ __global__ void __launch_bounds__(256) allocate_kernel(AllocArgs a) {
   if (tid < L) {
     const int s = S[tid];
     const int m = max(min(a.W, s), (int)(((long long)s * a.num) / a.den));
-    long long o = 0;
+    long long o = (long long)n * a.B;
     for (int j = 0; j < tid; ++j) o += S[j];
-    a.alloc[4 * tid + 0] = s;
-    a.alloc[4 * tid + 1] = m;
-    a.alloc[4 * tid + 2] = s - m;
+    const int lv = n * L + tid;  // layer of the batch
+    a.alloc[4 * lv + 0] = s;
+    a.alloc[4 * lv + 1] = m;
+    a.alloc[4 * lv + 2] = s - m;
     // layers ranked by decreasing budget (ties: lower layer first), for kernels that launch the
-    // longest workgroups first
+    // longest workgroups first; in a batch the ranks of the sequences are interleaved (rank r of
+    // sequence n is entry r*N + n), which keeps the order of one sequence and is decreasing on average
     int rank = 0;
     for (int j = 0; j < L; ++j) rank += (S[j] > s || (S[j] == s && j < tid)) ? 1 : 0;
-    a.alloc[4 * rank + 3] = tid;
-    a.off[tid] = o;
-    a.layer_len[tid] = s;
-    a.layer_off[tid] = o;
+    a.alloc[4 * (rank * a.N + n) + 3] = lv;
+    a.off[lv] = o;
+    a.layer_len[lv] = s;
+    a.layer_off[(size_t)n * (L + 1) + tid] = o;
     if (tid == L - 1) {
-      a.off[L] = o + s;
-      a.layer_off[L] = o + s;
+      if (n == a.N - 1) a.off[(size_t)a.N * L] = o + s;
+      a.layer_off[(size_t)n * (L + 1) + L] = o + s;
     }
   }
 }
@@ -161,6 +169,7 @@ struct SelectArgs {
   int32_t* less_idx;        // ragged [(L*T-B)*Hkv]: row ids
   int32_t* merge_assign;    // may be null, [L][Hkv][T]
   int L, Hkv, T, no_merge;
+  int Lseq;                 // layers per sequence (the mask is per sequence)
 };
 
 constexpr int kSelMaxThreads = 1024;
@@ -191,6 +200,7 @@ __global__ void __launch_bounds__(kSelMaxThreads) select_kernel(SelectArgs a) {
   const int g = blockIdx.x, l = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int kSelThreads = blockDim.x, kSelWaves = kSelThreads >> 6;
   const int T = a.T;
+  const uint8_t* mask = a.mask + (size_t)(l / a.Lseq) * T;  // this layer's sequence
   const int S = a.alloc[4 * l + 0], M = a.alloc[4 * l + 1], N = a.alloc[4 * l + 2];
   const int ncand = T - M;
   const long long off_l = a.off[l];
@@ -201,7 +211,7 @@ __global__ void __launch_bounds__(kSelMaxThreads) select_kernel(SelectArgs a) {
 
   // number of text candidates
   int cnt = 0;
-  for (int j = tid; j < ncand; j += kSelThreads) cnt += (a.mask[j] == 0) ? 1 : 0;
+  for (int j = tid; j < ncand; j += kSelThreads) cnt += (mask[j] == 0) ? 1 : 0;
   cnt = wave_sum(cnt);
   if (lane == 0) s_red[wave] = cnt;
   __syncthreads();
@@ -223,7 +233,7 @@ __global__ void __launch_bounds__(kSelMaxThreads) select_kernel(SelectArgs a) {
       __syncthreads();
       const unsigned prefix = s_prefix;
       for (int j = tid; j < ncand; j += kSelThreads) {
-        if ((a.mask[j] != 0) == (cls != 0)) {
+        if ((mask[j] != 0) == (cls != 0)) {
           const unsigned key = __float_as_uint(scores[j]);
           if ((key & prefix_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
         }
@@ -270,7 +280,7 @@ __global__ void __launch_bounds__(kSelMaxThreads) select_kernel(SelectArgs a) {
     const bool valid = j < T;
     bool in_cls = false, is_tie = false, above = false;
     if (valid && j < ncand) {
-      in_cls = (a.mask[j] != 0) == (cls != 0);
+      in_cls = (mask[j] != 0) == (cls != 0);
       if (in_cls) {
         const unsigned key = __float_as_uint(scores[j]);
         above = key > threshold;
@@ -322,9 +332,10 @@ hipError_t launch_allocate(const Plan& p, const Buffers& b, hipStream_t s) {
   a.layer_len = b.layer_len;
   a.layer_off = b.layer_off;
   a.entropy = b.entropy;
-  a.L = p.L; a.NT = p.NTk; a.T = p.T; a.W = p.W; a.R = p.R; a.num = p.num; a.den = p.den; a.flags = p.flags;
-  a.B = p.B;
-  hipLaunchKernelGGL(allocate_kernel, dim3(1), dim3(256), 0, s, a);
+  a.L = p.Lseq; a.NT = p.NTk; a.T = p.T; a.W = p.W; a.R = p.R; a.num = p.num; a.den = p.den; a.flags = p.flags;
+  a.N = p.N;
+  a.B = p.B / p.N;
+  hipLaunchKernelGGL(allocate_kernel, dim3(p.N), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 
@@ -341,6 +352,7 @@ hipError_t launch_select(const Plan& p, const Buffers& b, hipStream_t s) {
   a.less_idx = reinterpret_cast<int32_t*>(b.ws + p.off_less_idx);
   a.merge_assign = b.merge_assign;
   a.L = p.L; a.Hkv = p.Hkv; a.T = p.T; a.no_merge = (p.flags & MEDA_FLAG_NO_MERGE) ? 1 : 0;
+  a.Lseq = p.Lseq;
   const int nthr = p.T >= 16384 ? 1024 : (p.T >= 4096 ? 512 : 256);
   hipLaunchKernelGGL(select_kernel, dim3(p.Hkv, p.L), dim3(nthr), 0, s, a);
   return hipGetLastError();

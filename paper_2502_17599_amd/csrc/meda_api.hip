@@ -55,13 +55,21 @@ meda_status make_plan(const meda_params* p, Plan* out) {
   if (!(p->softmax_scale >= 0.0f) || !isfinite(p->softmax_scale)) return MEDA_ERR_INVALID_ARG;
   if (p->dtype != MEDA_F32 && p->dtype != MEDA_BF16) return MEDA_ERR_UNSUPPORTED;
   if (p->head_dim != 64 && p->head_dim != 128) return MEDA_ERR_UNSUPPORTED;
-  if (p->n_layers > kMaxLayers || p->window > 128) return MEDA_ERR_UNSUPPORTED;
-  if ((int64_t)p->n_layers * p->n_kv_heads * (int64_t)p->seq_len >= (1ll << 31)) return MEDA_ERR_UNSUPPORTED;
-  if ((int64_t)p->n_layers * p->n_q_heads * 128 >= (1ll << 31)) return MEDA_ERR_UNSUPPORTED;
+  if (p->n_seqs < 0) return MEDA_ERR_INVALID_ARG;
+  const int n_seqs = p->n_seqs > 0 ? p->n_seqs : 1;
+  const int64_t layers = (int64_t)n_seqs * p->n_layers;  // layers of the whole batch
+  if (layers > kMaxLayers || p->window > 128) return MEDA_ERR_UNSUPPORTED;
+  if (layers * p->n_kv_heads * (int64_t)p->seq_len >= (1ll << 31)) return MEDA_ERR_UNSUPPORTED;
+  if (layers * p->n_q_heads * 128 >= (1ll << 31)) return MEDA_ERR_UNSUPPORTED;
+  {
+    const int64_t lo1 = (int64_t)p->n_layers * (p->window < p->seq_len ? p->window : p->seq_len);
+    if (p->total_budget < lo1 || p->total_budget > (int64_t)p->n_layers * p->seq_len) return MEDA_ERR_BUDGET;
+  }
 
   Plan pl;
-  pl.L = p->n_layers; pl.Hq = p->n_q_heads; pl.Hkv = p->n_kv_heads; pl.G = pl.Hq / pl.Hkv;
-  pl.d = p->head_dim; pl.T = p->seq_len; pl.W = p->window; pl.B = p->total_budget;
+  pl.N = n_seqs; pl.Lseq = p->n_layers;
+  pl.L = (int)layers; pl.Hq = p->n_q_heads; pl.Hkv = p->n_kv_heads; pl.G = pl.Hq / pl.Hkv;
+  pl.d = p->head_dim; pl.T = p->seq_len; pl.W = p->window; pl.B = p->total_budget * n_seqs;
   pl.num = p->recent_num; pl.den = p->recent_den; pl.dtype = p->dtype; pl.flags = p->flags;
   pl.elt = (p->dtype == MEDA_BF16) ? 2 : 4;
   const int64_t lo = (int64_t)pl.L * (pl.W < pl.T ? pl.W : pl.T), hi = (int64_t)pl.L * pl.T;

@@ -19,8 +19,11 @@ constexpr int kMaxLayers = 256;
 constexpr int kScoreRowBlock = 128;  // query rows per scoring launch when every prompt row scores
 
 struct Plan {
-  // problem
+  // problem.  A batch of N sequences is laid out as N * Lseq "layers": every kernel but the budget
+  // allocation treats layers independently, so L and B below are totals over the batch and only the
+  // modality mask (one per sequence: layer l uses mask + (l / Lseq) * T) and the allocation know about sequences.
   int L, Hq, Hkv, G, d, T, W;
+  int N, Lseq;
   int64_t B;
   int num, den, dtype, flags;
   float scale_log2;  // softmax scale times log2(e): logits are kept in the base-2 domain

@@ -19,13 +19,14 @@ namespace meda {
 struct ScoreArgs {
   const char* q;
   const char* k;
-  const uint8_t* mask;
+  const uint8_t* mask;  // [N][Tk]: layer l belongs to sequence l / Lseq
   float4* stats_part;  // [L][Hq][Wp][NPART] (max, Z_vision, Z_text, -)
   float4* stats;       // [L][Hq][Wp]        (max, 1/Z_all, coef for vision columns, coef for text columns)
   float* inv_norm;     // [L][Hkv][T]
   float* col_scores;   // [L][Hkv][T]
   double* ent_part;    // [L][NT][2]
   int L, Hq, Hkv, G, T, W, RB, Wp;   // T keys and W query rows of this launch (the last W positions below T)
+  int Lseq;        // layers per sequence
   int NCG, CS, CH, NPART, NT;
   int Tk;          // key rows per (layer, kv head) in memory (>= T)
   int q_rows;      // rows per (layer, head) in the query buffer
@@ -81,6 +82,7 @@ __global__ void __launch_bounds__(NW * 64, (NQ == 1 && NW == 4 && sizeof(T) == 2
     }
   }
 
+  const uint8_t* mask = a.mask + (size_t)(l / a.Lseq) * a.Tk;  // this layer's sequence
   const int jbeg = ch * a.CH;
   const int jend = min(a.T, jbeg + a.CH);
   const char* kbase = a.k + (size_t)(l * a.Hkv + g) * a.Tk * TL::kRowBytes;
@@ -90,7 +92,7 @@ __global__ void __launch_bounds__(NW * 64, (NQ == 1 && NW == 4 && sizeof(T) == 2
   uint8_t mreg = 0;
   if (jbeg < jend) {
     stage.template fetch<true>(kbase + (size_t)jbeg * TL::kRowBytes, min(kScoreTile, a.T - jbeg), tid, nthr);
-    if (tid < kScoreTile) mreg = (jbeg + tid < a.T) ? a.mask[jbeg + tid] : 0;
+    if (tid < kScoreTile) mreg = (jbeg + tid < a.T) ? mask[jbeg + tid] : 0;
   }
   for (int j0 = jbeg; j0 < jend; j0 += kScoreTile) {
     __syncthreads();  // the previous tile is no longer read
@@ -101,7 +103,7 @@ __global__ void __launch_bounds__(NW * 64, (NQ == 1 && NW == 4 && sizeof(T) == 2
     if (j0 + kScoreTile < jend) {  // next tile's loads are in flight while this one is processed
       const int jn = j0 + kScoreTile;
       stage.template fetch<true>(kbase + (size_t)jn * TL::kRowBytes, min(kScoreTile, a.T - jn), tid, nthr);
-      if (tid < kScoreTile) mreg = (jn + tid < a.T) ? a.mask[jn + tid] : 0;
+      if (tid < kScoreTile) mreg = (jn + tid < a.T) ? mask[jn + tid] : 0;
     }
 
     // 1/|k| of the tile's keys: two threads per row
@@ -223,7 +225,8 @@ __global__ void __launch_bounds__(256) stats_combine_kernel(ScoreArgs a) {
     zv = fmaf(p.y, f, zv);
     zt = fmaf(p.z, f, zt);
   }
-  const bool row_is_vision = a.mask[a.T - a.W + row] != 0;
+  const int l = idx / (a.Hq * a.Wp);
+  const bool row_is_vision = a.mask[(size_t)(l / a.Lseq) * a.Tk + a.T - a.W + row] != 0;
   const float coef_v = (!row_is_vision && zv > 0.f) ? 1.0f / zv : 0.f;  // text row: attends to vision columns
   const float coef_t = (row_is_vision && zt > 0.f) ? 1.0f / zt : 0.f;   // vision row: attends to text columns
   a.stats[idx] = make_float4(M, 1.0f / (zv + zt), coef_v, coef_t);
@@ -263,7 +266,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 8) ? 2 : ((RB == 1 && sizeof(T
   const int j0 = tile * kScoreTile;
   const int j = j0 + cw * 32 + n;  // this lane's key column
   const bool col_ok = j < a.T;
-  const bool col_is_vision = col_ok && a.mask[j] != 0;
+  const bool col_is_vision = col_ok && a.mask[(size_t)(l / a.Lseq) * a.Tk + j] != 0;
   const float* st_coef = col_is_vision ? st_cv : st_ct;
   const bool full = j0 + kScoreTile - 1 <= a.T - a.W;
   const int rows_valid = min(kScoreTile, a.T - j0);
@@ -431,7 +434,7 @@ static ScoreArgs make_args(const Plan& p, const Buffers& b) {
   a.col_scores = reinterpret_cast<float*>(b.ws + p.off_col_scores);
   a.ent_part = reinterpret_cast<double*>(b.ws + p.off_ent_part);
   a.L = p.L; a.Hq = p.Hq; a.Hkv = p.Hkv; a.G = p.G; a.T = p.Tb; a.W = p.Wb; a.RB = p.RB; a.Wp = p.Wp;
-  a.Tk = p.Tk; a.q_rows = p.R; a.q_row0 = p.q_row0; a.NTk = p.NTk; a.accumulate = p.accumulate;
+  a.Lseq = p.Lseq; a.Tk = p.Tk; a.q_rows = p.R; a.q_row0 = p.q_row0; a.NTk = p.NTk; a.accumulate = p.accumulate;
   a.NCG = p.NCG; a.CS = p.CS; a.CH = p.CH; a.NPART = p.NPART; a.NT = p.NT;
   a.c = p.scale_log2;
   return a;

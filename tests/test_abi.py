@@ -31,6 +31,7 @@ def test_every_declared_symbol_is_exported(lib):
 def test_params_struct_matches_header_layout():
     assert ctypes.sizeof(pkg.MedaParams) == 56
     assert pkg.MedaParams.total_budget.offset == 24 and pkg.MedaParams.flags.offset == 48
+    assert pkg.MedaParams.n_seqs.offset == 52
 
 
 def _params(**kw):
@@ -46,8 +47,12 @@ def test_workspace_bytes_valid_and_invalid(lib):
     for bad in (dict(n_layers=0), dict(n_q_heads=7), dict(head_dim=96), dict(window=0), dict(window=2000),
                 dict(total_budget=4 * 31), dict(total_budget=4 * 1000 + 1), dict(recent_den=0),
                 dict(recent_num=5, recent_den=4), dict(dtype=7), dict(window=129, seq_len=4096, total_budget=4 * 500),
-                dict(n_layers=300, total_budget=300 * 250)):
+                dict(n_layers=300, total_budget=300 * 250), dict(n_seqs=-1), dict(n_seqs=65)):
         assert pkg.meda_workspace_bytes(_params(**bad)) == 0, bad
+    # a batch: the workspace grows with the number of sequences (64 x 4 layers is the largest batch of this shape)
+    one, four = pkg.meda_workspace_bytes(_params()), pkg.meda_workspace_bytes(_params(n_seqs=4))
+    assert pkg.meda_workspace_bytes(_params(n_seqs=1)) == one and 3 * one < four <= 4 * one + 4096
+    assert pkg.meda_workspace_bytes(_params(n_seqs=64)) > 0
 
 
 def _status(lib, params, ptrs, ws_bytes):

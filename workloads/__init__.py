@@ -11,7 +11,7 @@ embeddings, or text followed by many video-frame embeddings).  Only shapes and
 structure are taken; no benchmark data is reproduced.
 """
 from .configs import Workload, WORKLOADS, get_workload, variant
-from .gen import generate, generate_layer, modality_mask
+from .gen import generate, generate_batch, generate_layer, modality_mask
 
 __all__ = ["Workload", "WORKLOADS", "get_workload", "variant",
-           "generate", "generate_layer", "modality_mask"]
+           "generate", "generate_batch", "generate_layer", "modality_mask"]

@@ -123,6 +123,13 @@ def generate(wl: Workload, layers: Optional[Iterable[int]] = None, threads: int 
     return {"q": q, "k": k, "v": v, "mask": torch.from_numpy(modality_mask(wl))}
 
 
+def generate_batch(wls, threads: int = 8) -> Dict[str, object]:
+    """Inputs of several workloads of one shape (they may differ in seed and in layout, not in any size),
+    stacked along a new leading dimension: ``q`` [N,L,Hq,R,d], ``k``, ``v`` [N,L,Hkv,T,d], ``mask`` [N,T]."""
+    parts = [generate(w, threads=threads) for w in wls]
+    return {key: torch.stack([p[key] for p in parts]).contiguous() for key in ("q", "k", "v", "mask")}
+
+
 def to_float64(t: torch.Tensor) -> np.ndarray:
     """Exact widening of a stored tensor (f32 or bf16) to a float64 numpy array."""
     return t.to(torch.float64).numpy()
