@@ -96,7 +96,18 @@ def decode_step_record(pkg, torch, wl, out, q_dtype, k, v, dev, iters=50):
     ms_f = timed(dec_f, q, k.view(-1, d), v.view(-1, d), full_len, full_off)
     bytes_c = 2.0 * wl.total_budget * Hkv * d * e
     bytes_f = 2.0 * L * T * Hkv * d * e
-    return {"compressed_ms": ms_c, "compressed_GBps": bytes_c / (ms_c * 1e-3) / 1e9,
+    fp8 = {}
+    if q_dtype == torch.bfloat16:   # the same step over the 8-bit storage of the compressed cache
+        def quantise():
+            return pkg.meda_quantize_fp8(out.k_out), pkg.meda_quantize_fp8(out.v_out)
+        (kc, ks), (vc, vs) = quantise()
+        ms_q = timed(lambda: quantise())
+        ms_8 = timed(dec.fp8, q, kc, vc, ks, vs, out.layer_len, out.layer_off)
+        bytes_8 = 2.0 * wl.total_budget * Hkv * (d + 4)      # codes and one scale per row
+        fp8 = {"compressed_fp8_ms": ms_8, "compressed_fp8_GBps": bytes_8 / (ms_8 * 1e-3) / 1e9,
+               "quantise_ms": ms_q,
+               "quantise_GBps": (bytes_c + bytes_8) / (ms_q * 1e-3) / 1e9}   # reads the bf16 rows, writes the codes
+    return {**fp8, "compressed_ms": ms_c, "compressed_GBps": bytes_c / (ms_c * 1e-3) / 1e9,
             "compressed_hbm_frac": bytes_c / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "full_cache_ms": ms_f, "full_cache_GBps": bytes_f / (ms_f * 1e-3) / 1e9,
             "full_cache_hbm_frac": bytes_f / (ms_f * 1e-3) / 1e9 / HBM_PEAK_GBS,

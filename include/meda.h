@@ -173,6 +173,39 @@ meda_status meda_decode_attention(const meda_decode_params* params, const void* 
                                   const void* k_new, const void* v_new, void* out, void* workspace,
                                   size_t workspace_bytes, void* hip_stream);
 
+/*
+ * 8-bit storage of a compressed cache.  The paper names quantisation of the KV cache as a technique that can be
+ * combined with its method (Limitations) and fixes no scheme; this one is the library's own.  Per row of
+ * head_dim elements:
+ *   scale  = max|x| / 448 in fp32 (1 for an all-zero row)
+ *   code_i = E4M3(clamp(x_i / scale, -448, 448)): fp32 division, round to nearest, ties to even, where E4M3 is
+ *            the 8-bit format of the OCP 8-bit floating point specification (1 sign, 4 exponent bits with
+ *            bias 7, 3 mantissa bits, no infinities, largest magnitude 448); a NaN code is never written
+ *   x_i   ~= value(code_i) * scale
+ * rows    [n_rows][head_dim] of `dtype` (meda_dtype), e.g. k_out or v_out of meda_compress (read-only)
+ * codes   [n_rows][head_dim] uint8, scales [n_rows] float (outputs)
+ * head_dim 64 or 128; n_rows >= 0; device pointers, 16-byte aligned; enqueued on hip_stream, nothing allocated.
+ * meda_dequantize_fp8 is the inverse map (one rounding to `dtype`; exact for MEDA_BF16 and MEDA_F32 up to the
+ * product with the scale).
+ */
+meda_status meda_quantize_fp8(const void* rows, int32_t dtype, int64_t n_rows, int32_t head_dim, uint8_t* codes,
+                              float* scales, void* hip_stream);
+meda_status meda_dequantize_fp8(const uint8_t* codes, const float* scales, int32_t dtype, int64_t n_rows,
+                                int32_t head_dim, void* rows, void* hip_stream);
+
+/*
+ * meda_decode_attention over a cache stored with meda_quantize_fp8: k_codes, v_codes [B*Hkv][d] uint8 and
+ * k_scales, v_scales [B*Hkv] float in the ragged layout of meda_compress; q, the appended rows k_new / v_new and
+ * out are of params->dtype, which must be MEDA_BF16 (MEDA_ERR_UNSUPPORTED otherwise).  The step computes
+ * Softmax(q K^T * scale) V with K = value(k_codes) * k_scales and V likewise (Section 3.1); it reads half the
+ * bytes of the bf16 cache.  Workspace and all other arguments as for meda_decode_attention.
+ */
+meda_status meda_decode_attention_fp8(const meda_decode_params* params, const void* q, const uint8_t* k_codes,
+                                      const uint8_t* v_codes, const float* k_scales, const float* v_scales,
+                                      const int32_t* layer_len, const int64_t* layer_off, const void* k_new,
+                                      const void* v_new, void* out, void* workspace, size_t workspace_bytes,
+                                      void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

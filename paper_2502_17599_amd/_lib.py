@@ -13,7 +13,8 @@ _LIB_NAME = "libmeda.so"
 
 EXPORTED_SYMBOLS = ("meda_workspace_bytes", "meda_compress", "meda_workspace_region",
                     "meda_profile_enable", "meda_profile_read", "meda_phase_name", "meda_status_string",
-                    "meda_decode_workspace_bytes", "meda_decode_attention")
+                    "meda_decode_workspace_bytes", "meda_decode_attention",
+                    "meda_quantize_fp8", "meda_dequantize_fp8", "meda_decode_attention_fp8")
 REGIONS = {"col_scores": 0, "inv_norm": 1, "row_stats": 2, "alloc": 3, "less_idx": 4, "less_slot": 5}
 N_PHASES = 8
 FLAG_UNIFORM_BUDGET = 1
@@ -81,6 +82,12 @@ def load_library() -> ctypes.CDLL:
     lib.meda_decode_workspace_bytes.argtypes = [dp]
     lib.meda_decode_attention.restype = ctypes.c_int
     lib.meda_decode_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.meda_quantize_fp8.restype = ctypes.c_int
+    lib.meda_quantize_fp8.argtypes = [vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, vp, vp, vp]
+    lib.meda_dequantize_fp8.restype = ctypes.c_int
+    lib.meda_dequantize_fp8.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, vp, vp]
+    lib.meda_decode_attention_fp8.restype = ctypes.c_int
+    lib.meda_decode_attention_fp8.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     _lib = lib
     return lib
 
@@ -265,6 +272,15 @@ class Decoder:
         dt = torch.bfloat16 if params.dtype == 1 else torch.float32
         self.out = torch.empty(params.n_layers, params.n_q_heads, params.head_dim, dtype=dt, device=self.device)
 
+    def fp8(self, q, k_codes, v_codes, k_scales, v_scales, layer_len, layer_off, k_new=None, v_new=None, stream=None):
+        """The step over a cache stored with meda_quantize_fp8 (bf16 queries only)."""
+        stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        _check(load_library().meda_decode_attention_fp8(
+            ctypes.byref(self.params), _ptr(q), _ptr(k_codes), _ptr(v_codes), _ptr(k_scales), _ptr(v_scales),
+            _ptr(layer_len), _ptr(layer_off), _ptr(k_new), _ptr(v_new), _ptr(self.out), _ptr(self.workspace),
+            self.workspace.numel(), ctypes.c_void_p(stream.cuda_stream)))
+        return self.out
+
     def __call__(self, q, k_cache, v_cache, layer_len, layer_off, k_new=None, v_new=None, stream=None):
         stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         _check(load_library().meda_decode_attention(
@@ -272,6 +288,33 @@ class Decoder:
             _ptr(k_new), _ptr(v_new), _ptr(self.out), _ptr(self.workspace), self.workspace.numel(),
             ctypes.c_void_p(stream.cuda_stream)))
         return self.out
+
+
+def meda_quantize_fp8(rows: torch.Tensor, stream=None):
+    """Row-wise 8-bit (E4M3) storage of ``rows`` [n, d]: returns (codes uint8 [n, d], scales float32 [n])."""
+    if rows.dim() != 2 or not rows.is_contiguous() or rows.dtype not in _DTYPES or not rows.is_cuda:
+        raise ValueError("rows: expected a contiguous 2-d float32 or bfloat16 tensor on the GPU")
+    n, d = rows.shape
+    codes = torch.empty((n, d), dtype=torch.uint8, device=rows.device)
+    scales = torch.empty(n, dtype=torch.float32, device=rows.device)
+    stream = stream if stream is not None else torch.cuda.current_stream(rows.device)
+    _check(load_library().meda_quantize_fp8(_ptr(rows), _DTYPES[rows.dtype], n, d, _ptr(codes), _ptr(scales),
+                                            ctypes.c_void_p(stream.cuda_stream)))
+    return codes, scales
+
+
+def meda_dequantize_fp8(codes: torch.Tensor, scales: torch.Tensor, dtype=torch.bfloat16, stream=None):
+    """The rows a quantised cache stands for, in ``dtype``."""
+    if codes.dim() != 2 or codes.dtype != torch.uint8 or not codes.is_contiguous() or not codes.is_cuda:
+        raise ValueError("codes: expected a contiguous 2-d uint8 tensor on the GPU")
+    n, d = codes.shape
+    if tuple(scales.shape) != (n,) or scales.dtype != torch.float32 or scales.device != codes.device:
+        raise ValueError("scales: expected float32 [n] on the same device")
+    rows = torch.empty((n, d), dtype=dtype, device=codes.device)
+    stream = stream if stream is not None else torch.cuda.current_stream(codes.device)
+    _check(load_library().meda_dequantize_fp8(_ptr(codes), _ptr(scales), _DTYPES[dtype], n, d, _ptr(rows),
+                                              ctypes.c_void_p(stream.cuda_stream)))
+    return rows
 
 
 def meda_decode_attention(q, cache: "CompressedCache", k_new=None, v_new=None, softmax_scale=0.0, stream=None):

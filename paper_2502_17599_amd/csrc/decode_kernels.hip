@@ -15,6 +15,7 @@
 
 #include "../../include/meda.h"
 #include "device_utils.hpp"
+#include "fp8.hpp"
 
 namespace meda {
 
@@ -36,7 +37,19 @@ struct DecodeArgs {
   int L, Hq, Hkv, G, n_new;
   int NS, NSN, NP;          // chunks of the cached rows, chunks of the appended rows, NS + NSN
   float scale_log2;
+  // 8-bit cache (FP8 instantiation): k_cache / v_cache hold E4M3 codes, one scale per row
+  const float* k_scale;     // [B*Hkv]
+  const float* v_scale;
+  int sp0;                  // chunk index of the launch's first workgroup (the appended rows of an 8-bit cache
+                            // are taken by a second launch of the plain kernel, which starts at NS)
 };
+
+// 8-byte load of data that is read once (see load16_stream)
+__device__ __forceinline__ uint2 load8_stream(const void* p) {
+  typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+  const u32x2_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
+  return make_uint2(t.x, t.y);
+}
 
 template <typename T>
 struct Elems;
@@ -164,7 +177,10 @@ __device__ __forceinline__ void row_all_gather(float mine, float (&w)[GP], int c
 // wave takes 64 / LPR rows per step; every lane group keeps, per query head of the group, the running
 // maximum, the normaliser and its piece of the weighted value sum over the rows it has seen.  GP is
 // the group size rounded up to a power of two (heads past G repeat head 0 and are not stored).
-template <typename T, int D, int GP>
+// FP8: the cached rows are E4M3 codes with one scale per row (8-byte pieces, converted to packed bf16 on
+// arrival, which is exact; the key's scale multiplies the logit, the value's scale the softmax weight); the
+// queries stay bf16 and the launch covers the cached rows only.
+template <typename T, int D, int GP, bool FP8>
 __global__ void __launch_bounds__(kDecThreads, 2) decode_partial_kernel(DecodeArgs a) {
   using TL = Tile<T, D>;
   using EL = Elems<T>;
@@ -172,25 +188,35 @@ __global__ void __launch_bounds__(kDecThreads, 2) decode_partial_kernel(DecodeAr
   constexpr int MS = 64 / LPR;
   constexpr int E = EL::kPerPiece;
   constexpr int U = 2;  // steps whose loads are issued together
+  static_assert(!FP8 || sizeof(T) == 2, "the 8-bit cache is read with bf16 queries");
+  constexpr size_t kCacheRowBytes = FP8 ? (size_t)D : (size_t)TL::kRowBytes;
+  constexpr int kCachePieceBytes = FP8 ? E : 16;
   __shared__ float red_o[kDecWaves][GP][D];
   __shared__ float red_m[kDecWaves][GP], red_z[kDecWaves][GP];
 
-  const int sp = blockIdx.x, g = blockIdx.y, l = blockIdx.z;
+  const int sp = blockIdx.x + a.sp0, g = blockIdx.y, l = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int sub = lane / LPR, cc = lane - sub * LPR;
 
   // the rows of this workgroup
   const char *kb, *vb;
+  const float *ksc = nullptr, *vsc = nullptr;
   int r_beg, r_end;
-  if (sp < a.NS) {
+  size_t row_bytes = kCacheRowBytes;
+  int piece_bytes = kCachePieceBytes;
+  if (FP8 || sp < a.NS) {
     const int S = a.layer_len[l];
     const int chunk = (S + a.NS - 1) / a.NS;
     r_beg = sp * chunk;
     r_end = min(S, r_beg + chunk);
-    const size_t base = ((size_t)a.layer_off[l] * a.Hkv + (size_t)g * S) * TL::kRowBytes;
-    kb = a.k_cache + base;
-    vb = a.v_cache + base;
+    const size_t row0 = (size_t)a.layer_off[l] * a.Hkv + (size_t)g * S;
+    kb = a.k_cache + row0 * kCacheRowBytes;
+    vb = a.v_cache + row0 * kCacheRowBytes;
+    if (FP8) {
+      ksc = a.k_scale + row0;
+      vsc = a.v_scale + row0;
+    }
   } else {
     const int chunk = (a.n_new + a.NSN - 1) / a.NSN;
     r_beg = (sp - a.NS) * chunk;
@@ -198,9 +224,11 @@ __global__ void __launch_bounds__(kDecThreads, 2) decode_partial_kernel(DecodeAr
     const size_t base = ((size_t)(l * a.Hkv + g) * a.n_new) * TL::kRowBytes;
     kb = a.k_new + base;
     vb = a.v_new + base;
+    row_bytes = TL::kRowBytes;
+    piece_bytes = 16;
   }
-  kb += cc * 16;
-  vb += cc * 16;
+  kb += cc * piece_bytes;
+  vb += cc * piece_bytes;
 
   // this lane's piece of the G queries, kept packed
   uint4 qp[GP];
@@ -218,14 +246,25 @@ __global__ void __launch_bounds__(kDecThreads, 2) decode_partial_kernel(DecodeAr
 
   for (int r0 = r_beg + wave * MS; r0 < r_end; r0 += U * kDecWaves * MS) {
     uint4 kv[U], vv[U];
+    float sck[U], scv[U];
     bool ok[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int r = r0 + u * kDecWaves * MS + sub;
       ok[u] = r < r_end;
-      const size_t ro = (size_t)min(r, r_end - 1) * TL::kRowBytes;  // rows past the end repeat the last one
-      kv[u] = load16_stream(kb + ro);
-      vv[u] = load16_stream(vb + ro);
+      const int rc = min(r, r_end - 1);  // rows past the end repeat the last one
+      const size_t ro = (size_t)rc * row_bytes;
+      if constexpr (FP8) {
+        const uint2 kc = load8_stream(kb + ro), vc = load8_stream(vb + ro);
+        sck[u] = ksc[rc];
+        scv[u] = vsc[rc];
+        kv[u] = e4m3x8_to_bf16x8(kc);          // keys as packed bf16 for the dot instruction
+        vv[u] = make_uint4(vc.x, vc.y, 0u, 0u);  // values stay codes until they are needed as floats
+      } else {
+        kv[u] = load16_stream(kb + ro);
+        vv[u] = load16_stream(vb + ro);
+        sck[u] = scv[u] = 1.0f;
+      }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -233,7 +272,7 @@ __global__ void __launch_bounds__(kDecThreads, 2) decode_partial_kernel(DecodeAr
 #pragma unroll
       for (int h = 0; h < GP; ++h) s[h] = EL::dot(qp[h], kv[u]);
       row_reduce_scatter<GP, LPR>(s, cc);
-      const float s1 = ok[u] ? s[0] * a.scale_log2 : kNegBig;
+      const float s1 = ok[u] ? (FP8 ? s[0] * sck[u] * a.scale_log2 : s[0] * a.scale_log2) : kNegBig;
       // a new maximum of some head in some lane group: rescale what that head has so far (rare after
       // the first rows)
       if (__ballot(s1 > m1) != 0ull) {
@@ -251,8 +290,15 @@ __global__ void __launch_bounds__(kDecThreads, 2) decode_partial_kernel(DecodeAr
       const float p1 = ok[u] ? __builtin_amdgcn_exp2f(s1 - m1) : 0.f;
       z1 += p1;
       float p[GP], vf[E];
-      row_all_gather<GP, LPR>(p1, p, cc);
-      EL::unpack(vv[u], vf);
+      row_all_gather<GP, LPR>(FP8 ? p1 * scv[u] : p1, p, cc);   // the value row's scale rides on its weight
+      if constexpr (FP8) {
+        e4m3x2_to_float(vv[u].x, false, vf[0], vf[1]);
+        e4m3x2_to_float(vv[u].x, true, vf[2], vf[3]);
+        e4m3x2_to_float(vv[u].y, false, vf[4], vf[5]);
+        e4m3x2_to_float(vv[u].y, true, vf[6], vf[7]);
+      } else {
+        EL::unpack(vv[u], vf);
+      }
 #pragma unroll
       for (int h = 0; h < GP; ++h)
 #pragma unroll
@@ -361,9 +407,28 @@ static meda_status make_decode_plan(const meda_decode_params* p, DecodePlan* pl)
 }
 
 template <typename T, int D, int GP>
-static hipError_t launch_decode_g(const DecodePlan& pl, const DecodeArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL((decode_partial_kernel<T, D, GP>), dim3(pl.NP, pl.Hkv, pl.L), dim3(kDecThreads), 0, s, a);
-  hipError_t e = hipGetLastError();
+static hipError_t launch_decode_g(const DecodePlan& pl, const DecodeArgs& a_in, hipStream_t s) {
+  DecodeArgs a = a_in;
+  hipError_t e;
+  if constexpr (sizeof(T) == 2) {
+    if (a.k_scale) {  // 8-bit cache: its rows first, then the appended bf16 rows with the plain kernel
+      a.sp0 = 0;
+      hipLaunchKernelGGL((decode_partial_kernel<T, D, GP, true>), dim3(pl.NS, pl.Hkv, pl.L), dim3(kDecThreads), 0, s, a);
+      e = hipGetLastError();
+      if (e != hipSuccess) return e;
+      if (pl.NSN > 0) {
+        a.sp0 = pl.NS;
+        hipLaunchKernelGGL((decode_partial_kernel<T, D, GP, false>), dim3(pl.NSN, pl.Hkv, pl.L), dim3(kDecThreads), 0, s, a);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+      }
+      hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(pl.Hq, pl.L), dim3(D), 0, s, a);
+      return hipGetLastError();
+    }
+  }
+  a.sp0 = 0;
+  hipLaunchKernelGGL((decode_partial_kernel<T, D, GP, false>), dim3(pl.NP, pl.Hkv, pl.L), dim3(kDecThreads), 0, s, a);
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(pl.Hq, pl.L), dim3(D), 0, s, a);
   return hipGetLastError();
@@ -388,15 +453,18 @@ size_t meda_decode_workspace_bytes(const meda_decode_params* params) {
   return meda::make_decode_plan(params, &pl) == MEDA_OK ? pl.ws_bytes : 0;
 }
 
-meda_status meda_decode_attention(const meda_decode_params* params, const void* q, const void* k_cache,
-                                  const void* v_cache, const int32_t* layer_len, const int64_t* layer_off,
-                                  const void* k_new, const void* v_new, void* out, void* workspace,
-                                  size_t workspace_bytes, void* hip_stream) {
+static meda_status decode_common(const meda_decode_params* params, const void* q, const void* k_cache,
+                                 const void* v_cache, const float* k_scale, const float* v_scale, bool fp8,
+                                 const int32_t* layer_len, const int64_t* layer_off, const void* k_new,
+                                 const void* v_new, void* out, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream) {
   using namespace meda;
   DecodePlan pl;
   const meda_status st = make_decode_plan(params, &pl);
   if (st != MEDA_OK) return st;
+  if (fp8 && pl.dtype != MEDA_BF16) return MEDA_ERR_UNSUPPORTED;
   if (!q || !k_cache || !v_cache || !layer_len || !layer_off || !out) return MEDA_ERR_INVALID_ARG;
+  if (fp8 && (!k_scale || !v_scale || (((uintptr_t)k_scale | (uintptr_t)v_scale) & 3u))) return MEDA_ERR_INVALID_ARG;
   if (pl.n_new > 0 && (!k_new || !v_new)) return MEDA_ERR_INVALID_ARG;
   const uintptr_t al = (uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)k_new | (uintptr_t)v_new;
   if (al & 15u) return MEDA_ERR_INVALID_ARG;  // rows are moved in 16-byte pieces
@@ -415,11 +483,31 @@ meda_status meda_decode_attention(const meda_decode_params* params, const void* 
   a.L = pl.L; a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.G = pl.G; a.n_new = pl.n_new;
   a.NS = pl.NS; a.NSN = pl.NSN; a.NP = pl.NP;
   a.scale_log2 = pl.scale_log2;
+  a.k_scale = fp8 ? k_scale : nullptr;
+  a.v_scale = fp8 ? v_scale : nullptr;
+  a.sp0 = 0;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   hipError_t e;
   if (pl.dtype == MEDA_BF16) e = pl.d == 128 ? launch_decode_t<bf16_t, 128>(pl, a, s) : launch_decode_t<bf16_t, 64>(pl, a, s);
   else e = pl.d == 128 ? launch_decode_t<float, 128>(pl, a, s) : launch_decode_t<float, 64>(pl, a, s);
   return e == hipSuccess ? MEDA_OK : MEDA_ERR_HIP;
+}
+
+meda_status meda_decode_attention(const meda_decode_params* params, const void* q, const void* k_cache,
+                                  const void* v_cache, const int32_t* layer_len, const int64_t* layer_off,
+                                  const void* k_new, const void* v_new, void* out, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream) {
+  return decode_common(params, q, k_cache, v_cache, nullptr, nullptr, false, layer_len, layer_off, k_new, v_new, out,
+                       workspace, workspace_bytes, hip_stream);
+}
+
+meda_status meda_decode_attention_fp8(const meda_decode_params* params, const void* q, const uint8_t* k_codes,
+                                      const uint8_t* v_codes, const float* k_scales, const float* v_scales,
+                                      const int32_t* layer_len, const int64_t* layer_off, const void* k_new,
+                                      const void* v_new, void* out, void* workspace, size_t workspace_bytes,
+                                      void* hip_stream) {
+  return decode_common(params, q, k_codes, v_codes, k_scales, v_scales, true, layer_len, layer_off, k_new, v_new, out,
+                       workspace, workspace_bytes, hip_stream);
 }
 
 }  // extern "C"

@@ -22,7 +22,7 @@ def lib():
 
 def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "meda.h")).read()
-    declared = set(re.findall(r"\b(meda_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(meda_[a-z0-9_]+)\s*\(", header))
     assert declared == set(pkg.EXPORTED_SYMBOLS)
     for name in declared:
         assert getattr(lib, name) is not None
@@ -139,3 +139,23 @@ def test_decode_workspace_and_argument_checks(lib):
     p0 = pkg.make_decode_params(4, 8, 2, 128, 1000, torch.bfloat16, n_new=0)
     ptrs = list(good); ptrs[5] = 0; ptrs[6] = 0
     assert call(p0, ptrs, 0) == 4                      # passes the pointer checks, stops at the workspace size
+
+
+def test_fp8_entry_points_validate_on_the_host(lib):
+    q = lib.meda_quantize_fp8
+    assert q(None, 1, 0, 128, None, None, None) == 0                 # nothing to do
+    assert q(None, 1, -1, 128, None, None, None) == 1
+    assert q(None, 1, 8, 128, None, None, None) == 1                 # null pointers
+    assert q(None, 1, 8, 96, None, None, None) == 3 and q(None, 5, 8, 128, None, None, None) == 3
+    assert q(ctypes.c_void_p(4096 + 8), 1, 8, 128, ctypes.c_void_p(4096), ctypes.c_void_p(4096), None) == 1   # misaligned
+    dq = lib.meda_dequantize_fp8
+    assert dq(None, None, 1, 0, 64, None, None) == 0 and dq(None, None, 1, 3, 64, None, None) == 1
+    assert dq(None, None, 1, 3, 100, None, None) == 3
+    # the 8-bit decoding step: bf16 queries only, scales required
+    p16 = pkg.make_decode_params(2, 4, 4, 128, 64, torch.bfloat16)
+    p32 = pkg.make_decode_params(2, 4, 4, 128, 64, torch.float32)
+    a = ctypes.c_void_p(4096)
+    f = lib.meda_decode_attention_fp8
+    assert f(ctypes.byref(p32), a, a, a, a, a, a, a, None, None, a, a, 1 << 30, None) == 3
+    assert f(ctypes.byref(p16), a, a, a, None, a, a, a, None, None, a, a, 1 << 30, None) == 1
+    assert f(ctypes.byref(p16), a, a, a, a, a, a, a, None, None, a, a, 16, None) == 4            # workspace too small
