@@ -114,7 +114,8 @@ typedef enum {
                                  1/Z over all visible keys, then the row's cross-modal 1/Z as the factor
                                  for vision columns (text rows, else 0) and for text columns (vision
                                  rows, else 0)                                                        */
-  MEDA_REGION_ALLOC = 3,      /* int32 [L][4]: S_l, M_l, N_l, layer of rank l by decreasing S    */
+  MEDA_REGION_ALLOC = 3,      /* int32 [L][4]: S_l, M_l, N_l, layer of rank l by decreasing S (with n_seqs = N
+                                 > 1: [N*L][4], ranks of the sequences interleaved)                  */
   MEDA_REGION_LESS_IDX = 4,   /* int32 ragged: layer l, head g at ((l*T - off[l])*Hkv + g*(T-S_l)): the keys
                                  that are not conserved, ascending, as row ids (l*Hkv+g)*T + position */
   MEDA_REGION_LESS_SLOT = 5   /* int32, same layout: slot each of them merges into                   */

@@ -122,6 +122,49 @@ def test_batch_grouped_heads_bf16_and_decode():
     assert err <= 1e-6 + 2.0 ** -9, err
 
 
+@pytest.mark.parametrize("cfg", [
+    dict(n_layers=1, n_q_heads=3, n_kv_heads=3, head_dim=64, dtype="f32", window=17, T=333, B=1 * 60, n=5, flags=0),
+    dict(n_layers=5, n_q_heads=8, n_kv_heads=1, head_dim=128, dtype="bf16", window=64, T=1500, B=5 * 700, n=2, flags=0),
+    dict(n_layers=2, n_q_heads=6, n_kv_heads=3, head_dim=128, dtype="bf16", window=32, T=700, B=2 * 90, n=3, flags=2),
+    dict(n_layers=4, n_q_heads=4, n_kv_heads=2, head_dim=64, dtype="bf16", window=40, T=2100, B=4 * 2100, n=2, flags=0),
+])
+def test_batch_other_shapes_match_single_calls(cfg):
+    """Odd sizes, one kv head, eviction instead of merging, a budget that keeps everything: a batch still
+    reproduces the single calls bit for bit (the single calls' own parity is covered elsewhere)."""
+    T = cfg["T"]
+    base = variant(get_workload("tiny"), name="batch_misc", n_layers=cfg["n_layers"], n_q_heads=cfg["n_q_heads"],
+                   n_kv_heads=cfg["n_kv_heads"], head_dim=cfg["head_dim"], dtype=cfg["dtype"], window=cfg["window"],
+                   total_budget=cfg["B"], layout=(("t", T // 5, -1), ("v", T - T // 5 - T // 7, 0), ("t", T // 7, -1)))
+    layouts = [base.layout]
+    for i in range(1, cfg["n"]):
+        a = T // (3 + i)
+        layouts.append((("v", a, 0), ("t", T - a, -1)) if i % 2 else (("t", a, -1), ("v", T - 2 * a, 0), ("t", a, -1)))
+    _check_against_single_and_oracle(_batch_workloads(base, layouts), flags=cfg["flags"], oracle=False)
+
+
+def test_batch_with_every_prompt_row_scoring():
+    """The batch dimension and MEDA_FLAG_FULL_PROMPT together (row blocks x sequences)."""
+    import paper_2502_17599_amd as pkg
+    base = variant(get_workload("tiny"), name="batch_fp", n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=64, dtype="f32",
+                   window=32, total_budget=2 * 120, layout=(("t", 60, -1), ("v", 200, 0), ("t", 40, -1)), score_rows=300)
+    layouts = [base.layout, (("v", 150, 0), ("t", 150, -1)), (("t", 20, -1), ("v", 100, 0), ("t", 180, -1))]
+    wls = _batch_workloads(base, layouts)
+    _, out = _check_against_single_and_oracle(wls, flags=pkg.FLAG_FULL_PROMPT, oracle=False)
+    # the oracle on one of the sequences (every row scores: q has T rows)
+    from workloads import generate
+    n = 1
+    data_n = generate(wls[n])
+    ref = meda_oracle.meda_compress(to_float64(data_n["q"]), to_float64(data_n["k"]), to_float64(data_n["v"]),
+                                    data_n["mask"].numpy(), base.total_budget, base.window, base.dtype)
+    seq = out.sequence(n)
+    np.testing.assert_allclose(seq.entropy.cpu().numpy(), ref["entropy"], rtol=1e-3)
+    if np.array_equal(seq.layer_len.cpu().numpy(), ref["S"]):
+        for l in range(base.n_layers):
+            _, _, idx_l = seq.layer(l)
+            for g in range(base.n_kv_heads):
+                assert idx_l[g].cpu().tolist() == ref["heads"][l][g]["idx_c"].tolist()
+
+
 def test_batch_limits():
     import paper_2502_17599_amd as pkg
     # 129 sequences of 2 layers exceed the 256 layers one call handles
