@@ -112,6 +112,13 @@ __device__ __forceinline__ uint4 load16_stream(const void* p) {
   return make_uint4(t.x, t.y, t.z, t.w);
 }
 
+// 16-byte store of data this kernel does not read again (same hint as load16_stream).
+__device__ __forceinline__ void store16_stream(void* p, const uint4& v) {
+  typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+  const u32x4_t t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, reinterpret_cast<u32x4_t*>(p));
+}
+
 // Copy `rows` consecutive rows (contiguous in global memory) into a padded LDS tile; rows at or
 // beyond `rows_valid` are zero-filled.
 template <typename T, int D>
