@@ -25,7 +25,7 @@ __device__ __forceinline__ double clampd(double v, double lo, double hi) { retur
 // One workgroup per sequence.  S_l = B * softmax_l(E_CM) when no bound is active; shares are kept inside
 // [min(W,T), T] by water-filling (x_l = clamp(lambda * w_l), sum x_l = B) and rounded by largest
 // remainder, so that sum_l S_l = B exactly.  All real arithmetic is double precision.
-__global__ void __launch_bounds__(256) allocate_kernel(AllocArgs a) {
+__global__ void __launch_bounds__(1024) allocate_kernel(AllocArgs a) {
   __shared__ double E[kMaxLayers], w[kMaxLayers], x[kMaxLayers], frac[kMaxLayers];
   __shared__ double kink[2 * kMaxLayers], filled[2 * kMaxLayers];
   __shared__ int S[kMaxLayers], order[kMaxLayers];
@@ -335,7 +335,7 @@ hipError_t launch_allocate(const Plan& p, const Buffers& b, hipStream_t s) {
   a.L = p.Lseq; a.NT = p.NTk; a.T = p.T; a.W = p.W; a.R = p.R; a.num = p.num; a.den = p.den; a.flags = p.flags;
   a.N = p.N;
   a.B = p.B / p.N;
-  hipLaunchKernelGGL(allocate_kernel, dim3(p.N), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(allocate_kernel, dim3(p.N), dim3(1024), 0, s, a);  // 16 waves share the per-layer sums of the entropy partials
   return hipGetLastError();
 }
 
