@@ -161,7 +161,9 @@ def check_all(wl, data, gpu, heads=None, score_layers=None, verbose=True):
         norms = np.linalg.norm(to_float64(k[l]), axis=-1)
         np.testing.assert_allclose(gpu["inv_norm"][l], 1.0 / np.maximum(norms, 1e-30), rtol=2e-6)
         e_ref = ent[l][2]
-        assert abs(gpu["entropy"][l] - e_ref) <= 1e-3 * abs(e_ref) + 1e-12, \
+        # 1e-3 relative; the floor covers entropies of almost one-hot rows, which lie below the resolution of fp32
+        # probabilities (1 - 2^-24): their absolute error of order 1e-8 moves no budget (S_l ~ exp(E))
+        assert abs(gpu["entropy"][l] - e_ref) <= 1e-3 * abs(e_ref) + 1e-7, \
             f"layer {l}: entropy {gpu['entropy'][l]} vs {e_ref}"
     stats["max_entropy_rel_err"] = max(abs(gpu["entropy"][l] - ent[l][2]) / max(abs(ent[l][2]), 1e-30) for l in ent)
     if len(ent) == L:

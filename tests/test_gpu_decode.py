@@ -62,7 +62,8 @@ def _check(wl, n_new=0, seed=11, layers=None):
         k_l = kc[a:a + Hkv * S[l]].reshape(Hkv, S[l], d); v_l = vc[a:a + Hkv * S[l]].reshape(Hkv, S[l], d)
         ref = D.decode_layer(qn[l], k_l, v_l, None if k_new is None else to_float64(k_new[l]),
                              None if v_new is None else to_float64(v_new[l]))
-        scale = max(np.abs(v_l).max(), 1e-30)
+        # the output is a convex combination of the cached and the appended value rows
+        scale = max(np.abs(v_l).max(), 0.0 if v_new is None else float(v_new[l].abs().max()), 1e-30)
         err = np.abs(got[l] - ref).max() / scale
         worst = max(worst, err)
         assert err <= tol, (l, err)

@@ -44,6 +44,25 @@ def _configs():
         out.append(variant(TINY, name=f"rand{i}", n_layers=L, n_q_heads=hkv * G, n_kv_heads=hkv, head_dim=d, dtype=dtype,
                            layout=_random_layout(r, T), window=W, total_budget=B, seed=100 + i, recent_num=num,
                            recent_den=den, tau_lo=0.3, tau_hi=3.0, heavy_frac=float(r.choice([0.0, 0.02, 0.1]))))
+    # a second draw with longer sequences (several sort tiles, both similarity kernels' regimes), windows of up to
+    # four 32-row blocks, group sizes up to 8 and more kv heads
+    r = np.random.Generator(np.random.Philox(key=[2024, 6]))
+    for i in range(14, 40):
+        T = int(r.choice([33, 100, 128, 129, 255, 256, 300, 513, 777, 1024, 1500, 2049, 3000]))
+        W = int(min(T, r.choice([1, 5, 31, 32, 33, 63, 64, 65, 96, 97, 127, 128])))
+        hkv = int(r.choice([1, 2, 3, 5]))
+        G = int(r.choice([1, 2, 3, 4, 6, 7, 8]))
+        while G * ((W + 31) // 32) > 32:
+            G -= 1
+        d = int(r.choice([64, 128]))
+        dtype = str(r.choice(["f32", "bf16"]))
+        L = int(r.integers(1, 4))
+        lo, hi = L * W, L * T
+        B = int(r.integers(lo, hi + 1)) if r.random() < 0.85 else int(r.choice([lo, hi]))
+        num, den = [(3, 4), (0, 1), (1, 1), (1, 2), (1, 3)][int(r.integers(0, 5))]
+        out.append(variant(TINY, name=f"rand{i}", n_layers=L, n_q_heads=hkv * G, n_kv_heads=hkv, head_dim=d, dtype=dtype,
+                           layout=_random_layout(r, T), window=W, total_budget=B, seed=100 + i, recent_num=num,
+                           recent_den=den, tau_lo=0.3, tau_hi=3.0, heavy_frac=float(r.choice([0.0, 0.02, 0.1]))))
     return out
 
 
