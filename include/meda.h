@@ -36,7 +36,9 @@ typedef enum {
   MEDA_ERR_BUDGET = 2,      /* total_budget outside [L*min(W,T), L*T]                               */
   MEDA_ERR_UNSUPPORTED = 3, /* head_dim / dtype / window / group size outside the built set         */
   MEDA_ERR_WORKSPACE = 4,   /* workspace null, misaligned or smaller than meda_workspace_bytes()    */
-  MEDA_ERR_HIP = 5          /* a HIP call or kernel launch failed                                    */
+  MEDA_ERR_HIP = 5,         /* a HIP call or kernel launch failed                                    */
+  MEDA_ERR_SCRATCH_LIMIT = 6 /* meda_decode_attention_noalloc: the step needs more scratch than the
+                               library's built-in array holds (MEDA_DECODE_NOALLOC_MAX_BYTES)        */
 } meda_status;
 
 typedef enum { MEDA_F32 = 0, MEDA_BF16 = 1 } meda_dtype;
@@ -173,6 +175,24 @@ meda_status meda_decode_attention(const meda_decode_params* params, const void* 
                                   const void* v_cache, const int32_t* layer_len, const int64_t* layer_off,
                                   const void* k_new, const void* v_new, void* out, void* workspace,
                                   size_t workspace_bytes, void* hip_stream);
+
+/*
+ * meda_decode_attention for callers that cannot allocate or hand over device scratch: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs, kernels and results as
+ * meda_decode_attention, without the workspace arguments: the chunk partials of the step live in a device array
+ * built into the library (MEDA_DECODE_NOALLOC_MAX_BYTES per GPU, held until the process ends).  The call
+ * allocates and frees nothing, on the host side of HIP or through any library.
+ *   - returns MEDA_ERR_SCRATCH_LIMIT, with nothing launched, when meda_decode_workspace_bytes(params) exceeds
+ *     MEDA_DECODE_NOALLOC_MAX_BYTES (the five benchmark shapes fit; the need grows with L * Hq * chunks)
+ *   - the array belongs to the current device of the calling thread, which must be the device of hip_stream
+ *   - all calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams,
+ *     or different threads) race; calls on one stream are ordered and safe.  Nothing in the array has to start
+ *     at zero: every partial a call reads was written by the same call.
+ */
+#define MEDA_DECODE_NOALLOC_MAX_BYTES (40u << 20)
+meda_status meda_decode_attention_noalloc(const meda_decode_params* params, const void* q, const void* k_cache,
+                                          const void* v_cache, const int32_t* layer_len, const int64_t* layer_off,
+                                          const void* k_new, const void* v_new, void* out, void* hip_stream);
 
 /*
  * 8-bit storage of a compressed cache.  The paper names quantisation of the KV cache as a technique that can be

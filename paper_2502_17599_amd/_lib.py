@@ -14,7 +14,9 @@ _LIB_NAME = "libmeda.so"
 EXPORTED_SYMBOLS = ("meda_workspace_bytes", "meda_compress", "meda_workspace_region",
                     "meda_profile_enable", "meda_profile_read", "meda_phase_name", "meda_status_string",
                     "meda_decode_workspace_bytes", "meda_decode_attention",
-                    "meda_quantize_fp8", "meda_dequantize_fp8", "meda_decode_attention_fp8")
+                    "meda_quantize_fp8", "meda_dequantize_fp8", "meda_decode_attention_fp8",
+                    "meda_decode_attention_noalloc")
+DECODE_NOALLOC_MAX_BYTES = 40 << 20
 REGIONS = {"col_scores": 0, "inv_norm": 1, "row_stats": 2, "alloc": 3, "less_idx": 4, "less_slot": 5}
 N_PHASES = 8
 FLAG_UNIFORM_BUDGET = 1
@@ -82,6 +84,8 @@ def load_library() -> ctypes.CDLL:
     lib.meda_decode_workspace_bytes.argtypes = [dp]
     lib.meda_decode_attention.restype = ctypes.c_int
     lib.meda_decode_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.meda_decode_attention_noalloc.restype = ctypes.c_int
+    lib.meda_decode_attention_noalloc.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.meda_quantize_fp8.restype = ctypes.c_int
     lib.meda_quantize_fp8.argtypes = [vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, vp, vp, vp]
     lib.meda_dequantize_fp8.restype = ctypes.c_int
@@ -288,6 +292,17 @@ class Decoder:
             _ptr(k_new), _ptr(v_new), _ptr(self.out), _ptr(self.workspace), self.workspace.numel(),
             ctypes.c_void_p(stream.cuda_stream)))
         return self.out
+
+
+def meda_decode_attention_noalloc(params: MedaDecodeParams, q, k_cache, v_cache, layer_len, layer_off, out,
+                                  k_new=None, v_new=None, stream=None):
+    """meda_decode_attention without a workspace: the library's built-in device array holds the chunk partials.
+    ``out`` [L][Hq][d] is written in place (the call itself allocates nothing)."""
+    stream = stream if stream is not None else torch.cuda.current_stream(q.device)
+    _check(load_library().meda_decode_attention_noalloc(
+        ctypes.byref(params), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(layer_len), _ptr(layer_off),
+        _ptr(k_new), _ptr(v_new), _ptr(out), ctypes.c_void_p(stream.cuda_stream)))
+    return out
 
 
 def meda_quantize_fp8(rows: torch.Tensor, stream=None):

@@ -13,6 +13,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/meda.h"
 #include "device_utils.hpp"
 #include "fp8.hpp"
@@ -444,6 +446,39 @@ static hipError_t launch_decode_t(const DecodePlan& pl, const DecodeArgs& a, hip
   }
 }
 
+// Scratch of the entry point that allocates nothing: the chunk partials of one decoding step live in this
+// file-scope device array instead of a caller-provided workspace.  Every GPU holds its own copy at its own
+// address; the name below is only the host-side handle of the symbol, the address a kernel can use is looked
+// up once per device (scratch_of_current_device) and kept.
+constexpr size_t kDecodeScratchBytes = (size_t)MEDA_DECODE_NOALLOC_MAX_BYTES;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kDecodeScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on the current device, or null (with *err set) if a HIP call failed.
+static void* scratch_of_current_device(hipError_t* err) {
+  int dev = -1;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= kMaxDevices) {
+    *err = hipErrorInvalidDevice;
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    *err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess || !ptr) {
+      if (*err == hipSuccess) *err = hipErrorInvalidSymbol;
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
 }  // namespace meda
 
 extern "C" {
@@ -499,6 +534,22 @@ meda_status meda_decode_attention(const meda_decode_params* params, const void* 
                                   size_t workspace_bytes, void* hip_stream) {
   return decode_common(params, q, k_cache, v_cache, nullptr, nullptr, false, layer_len, layer_off, k_new, v_new, out,
                        workspace, workspace_bytes, hip_stream);
+}
+
+meda_status meda_decode_attention_noalloc(const meda_decode_params* params, const void* q, const void* k_cache,
+                                          const void* v_cache, const int32_t* layer_len, const int64_t* layer_off,
+                                          const void* k_new, const void* v_new, void* out, void* hip_stream) {
+  meda::DecodePlan pl;
+  const meda_status st = meda::make_decode_plan(params, &pl);
+  if (st != MEDA_OK) return st;
+  if (pl.ws_bytes > meda::kDecodeScratchBytes) return MEDA_ERR_SCRATCH_LIMIT;
+  hipError_t err = hipSuccess;
+  void* ptr = meda::scratch_of_current_device(&err);
+  if (!ptr) return MEDA_ERR_HIP;
+  // every chunk partial the combine kernel reads is written by the partial kernel of the same call (also for
+  // chunks without rows), so nothing in the array has to be cleared between calls
+  return decode_common(params, q, k_cache, v_cache, nullptr, nullptr, false, layer_len, layer_off, k_new, v_new, out,
+                       ptr, meda::kDecodeScratchBytes, hip_stream);
 }
 
 meda_status meda_decode_attention_fp8(const meda_decode_params* params, const void* q, const uint8_t* k_codes,

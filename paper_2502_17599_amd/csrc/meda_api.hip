@@ -274,6 +274,7 @@ const char* meda_status_string(meda_status status) {
     case MEDA_ERR_UNSUPPORTED: return "unsupported head_dim, dtype, window or group size";
     case MEDA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case MEDA_ERR_HIP: return "HIP error";
+    case MEDA_ERR_SCRATCH_LIMIT: return "the step needs more scratch than the no-allocation entry point's built-in array holds";
   }
   return "unknown status";
 }
