@@ -3,14 +3,18 @@
 
 One step = one meda_compress call: every phase of the pass over all layers and heads of one synthetic
 sequence whose inputs are already resident in HBM.  Prints one JSON line with the whole-job throughput
-(context tokens compressed per second), the roofline figures of the dominant kernel (HIP-event time of
-that kernel measured inside the timed region) and the CPU oracle timed on the host cores.
+(context tokens compressed per second) of the headline workload (the largest configuration, ``extreme``,
+unless --workload names another), the roofline figures of its dominant kernel (HIP-event time of that kernel
+measured inside the timed region), short runs of the other configurations (``per_workload``), the rates the
+chip delivers to a plain read stream and to back-to-back matrix instructions (``measured_peak``), and the CPU
+oracle timed on the host cores (``cpu_baseline``).
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -20,8 +24,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
-# kernels a phase launches (the similarity step is one launch of each of its two kernels: a layer goes to the
-# resident-set kernel when its conserved keys fit into LDS, else to the tiled one)
+HEADLINE = "extreme"
+# kernels a phase launches
 PHASE_KERNELS = {"score_stats": ["score_stats_kernel"], "stats_combine": ["stats_combine_kernel"],
                  "score_accum": ["score_accum_kernel"], "allocate": ["allocate_kernel"], "select": ["select_kernel"],
                  "similarity": ["similarity_argmax_kernel", "similarity_resident_kernel"],
@@ -30,7 +34,7 @@ PHASE_BOUND = {"score_stats": "hbm", "score_accum": "hbm", "similarity": "mfma",
                "select": "hbm", "segment_sort": "hbm", "stats_combine": "hbm", "allocate": "hbm"}
 
 
-def algorithmic_work(wl, budgets):
+def algorithmic_work(wl, budgets, full_prompt=False):
     """Per launch: bytes the method itself must move (hbm phases) or flops it must do (similarity; the
     scoring when every prompt row scores: the logits of the causal triangle once)."""
     L, Hkv, T, d = wl.n_layers, wl.n_kv_heads, wl.seq_len, wl.head_dim
@@ -38,7 +42,6 @@ def algorithmic_work(wl, budgets):
     k_bytes = L * Hkv * T * d * e
     out_rows = int(sum(budgets)) * Hkv
     less = [(T - s) * Hkv for s in budgets]
-    full_prompt = wl.n_score_rows == T and T != wl.window
     return {
         "score_stats": (1.0 * L * wl.n_q_heads * T * (T + 1) * d) if full_prompt else k_bytes,   # flops / every key once
         "score_accum": k_bytes,                                    # every key once
@@ -51,20 +54,98 @@ def algorithmic_work(wl, budgets):
     }
 
 
-def measured_traffic(workload, kernel):
-    """HBM bytes per launch of ``kernel`` from the committed rocprofv3 counter summary of this workload
-    (FETCH_SIZE and WRITE_SIZE, already scaled by the plain-copy calibration), or None."""
-    path = os.path.join(ROOT, "profiles", f"hbm_counters_{workload}.md")
-    if not os.path.exists(path):
-        return None
-    for line in open(path):
-        cells = [c.strip() for c in line.strip().strip("|").split("|")]
-        if len(cells) >= 4 and cells[0] == kernel:
-            try:
-                return float(cells[1]) + float(cells[2])
-            except ValueError:
-                return None
-    return None
+def time_pass(pkg, torch, wl, dev, steps, warmup, flags=0, n_seqs=0, phase_events=True, keep=False):
+    """Generates the workload, uploads it and times ``steps`` passes.  Returns the record fields of this
+    workload and, with ``keep``, the device tensors and the output object (for the decoding-step measurement)."""
+    from workloads import generate, generate_batch, variant
+    full_prompt = bool(flags & pkg.FLAG_FULL_PROMPT)
+    if n_seqs:
+        data = generate_batch([variant(wl, seed=wl.seed + i) for i in range(n_seqs)], threads=16)
+    else:
+        data = generate(wl, threads=16)
+    q, k, v, mask = (data[n].to(dev) for n in ("q", "k", "v", "mask"))
+    del data
+    params = pkg.make_params(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.seq_len, wl.window,
+                             wl.total_budget, q.dtype, wl.recent_num, wl.recent_den, 0.0, flags, n_seqs)
+    comp = pkg.Compressor(params, dev, want_entropy=True, want_sel_idx=True, want_merge_assign=False)
+    stream = torch.cuda.current_stream(dev)
+
+    names = [pkg.meda_phase_name(i) for i in range(pkg.N_PHASES)]
+    phase_kernels = dict(PHASE_KERNELS)
+    phase_bound = dict(PHASE_BOUND)
+    if full_prompt:            # the three scoring kernels are timed as one phase
+        phase_bound["score_stats"] = "mfma"
+        phase_kernels["score_stats"] = ["score_stats_kernel", "stats_combine_kernel", "score_accum_kernel"]
+    # warm-up with every kernel bracketed by events: gives the per-phase times and names the dominant kernel
+    comp(q, k, v, mask, stream)            # first call loads the code objects: not part of any figure
+    torch.cuda.synchronize()
+    pkg.meda_profile_enable(True)
+    pkg.meda_profile_read(reset=True)
+    for _ in range(max(warmup, 1)):
+        comp(q, k, v, mask, stream)
+    torch.cuda.synchronize()
+    warm_ms, warm_calls = pkg.meda_profile_read(reset=True)
+    per_phase = {n: warm_ms[i] / warm_calls for i, n in enumerate(names)}
+    dom = max(names, key=lambda n: per_phase[n])
+    # timed region: only the dominant kernel is bracketed (two events per call), on the stream it is launched on;
+    # one more event per step on the same stream gives the per-step times whose median is reported as well
+    pkg.meda_profile_enable(phase_events, names.index(dom))
+    step_ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    step_ev[0].record(stream)
+    for i in range(steps):
+        out = comp(q, k, v, mask, stream)
+        step_ev[i + 1].record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    phase_ms, n_calls = pkg.meda_profile_read(reset=True)
+    pkg.meda_profile_enable(False)
+    dom_ms = phase_ms[names.index(dom)] / n_calls if n_calls else None
+    step_ms = [step_ev[i].elapsed_time(step_ev[i + 1]) for i in range(steps)]
+
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    seqs = max(n_seqs, 1)
+    budgets = out.layer_len.cpu().reshape(seqs, wl.n_layers).tolist()
+    work = {}
+    for b in budgets:          # the sequences of a batch are independent: their work adds up
+        for key, val in algorithmic_work(wl, b, full_prompt).items():
+            work[key] = work.get(key, 0) + val
+
+    roofline = None
+    if dom_ms:
+        bound = phase_bound[dom]
+        t_s = dom_ms * 1e-3
+        if bound == "mfma":
+            achieved, peak, unit = work[dom] / t_s / 1e12, MFMA_PEAK_TFLOPS[wl.dtype], "TFLOP/s"
+        else:
+            achieved, peak, unit = work[dom] / t_s / 1e9, HBM_PEAK_GBS, "GB/s"
+        roofline = {"kernel": dom, "launches": phase_kernels[dom], "bound": bound, "achieved": achieved,
+                    "peak": peak, "unit": unit, "frac": achieved / peak,
+                    # HBM bytes per launch are not measured by this program: the counter runs are separate
+                    # rocprofv3 runs whose summaries are kept under profiles/
+                    "traffic": None, "traffic_source": f"profiles/hbm_counters_{wl.name}.md (rocprofv3 --pmc runs)",
+                    "work_per_launch": work[dom], "work_unit": "flop" if bound == "mfma" else "bytes",
+                    "kernel_ms": dom_ms, "launches_timed": n_calls}
+
+    alg_bytes = work["merge_write"]        # K and V once + the output: the traffic of the whole pass
+    score_flop = 2.0 * seqs * wl.n_layers * wl.n_q_heads * wl.window * wl.seq_len * wl.head_dim
+    rec = {
+        "value": seqs * wl.seq_len / (ms_per_step * 1e-3), "ms_per_step": ms_per_step,
+        "ms_per_step_event_median": statistics.median(step_ms),
+        "config": {"workload": wl.name + ("+full_prompt_scoring" if full_prompt else ""), "layers": wl.n_layers,
+                   "q_heads": wl.n_q_heads, "kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim,
+                   "seq_len": wl.seq_len, "window": wl.window, "total_budget": wl.total_budget, "seed": wl.seed,
+                   "batch": seqs},
+        "dtype": wl.dtype,
+        "kv_rows_per_sec": seqs * wl.n_layers * wl.n_kv_heads * wl.seq_len / (ms_per_step * 1e-3),
+        "pass_hbm_frac": (alg_bytes / (ms_per_step * 1e-3)) / (HBM_PEAK_GBS * 1e9),
+        "pass_mfma_frac": ((work["similarity"] + score_flop) / (ms_per_step * 1e-3)) / (MFMA_PEAK_TFLOPS[wl.dtype] * 1e12),
+        "phase_ms_warmup": per_phase,
+        "roofline": roofline,
+    }
+    kept = (q, k, v, out, budgets[0]) if keep else None
+    return rec, kept
 
 
 def decode_step_record(pkg, torch, wl, out, q_dtype, k, v, dev, iters=50):
@@ -114,21 +195,73 @@ def decode_step_record(pkg, torch, wl, out, q_dtype, k, v, dev, iters=50):
             "speedup": ms_f / ms_c, "cache_bytes_ratio": bytes_c / bytes_f}
 
 
-def cpu_baseline(wl, seconds_target=20.0):
-    """The fp64 oracle on a bounded sample: the first n layers of the same workload with the budget
-    scaled to n layers, n chosen from a one-layer probe so the run takes roughly ``seconds_target``."""
+def measured_peaks(pkg, torch, dev):
+    """What this chip delivers to the simplest kernels: a read stream over 2 GiB and back-to-back bf16 matrix
+    instructions from registers (median of 5 launches each, after one untimed launch)."""
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    buf = torch.empty(2 << 30, dtype=torch.uint8, device=dev).fill_(1)
+
+    def median_ms(fn, n=5):
+        fn()
+        torch.cuda.synchronize()
+        times = []
+        for _ in range(n):
+            e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+            e0.record(); fn(); e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+        return statistics.median(times)
+
+    ms_read = median_ms(lambda: pkg.meda_peak_stream_read(buf, sink))
+    total = [0]
+
+    def mfma():
+        total[0] = pkg.meda_peak_mfma_bf16(1 << 16, sink)
+    ms_mfma = median_ms(mfma)
+    del buf
+    return {"hbm_read_GBps": (2 << 30) / (ms_read * 1e-3) / 1e9,
+            "bf16_mfma_TFLOPs": total[0] * 32768.0 / (ms_mfma * 1e-3) / 1e12,
+            "published": {"hbm_GBps": HBM_PEAK_GBS, "bf16_mfma_TFLOPs": MFMA_PEAK_TFLOPS["bf16"]},
+            "how": "meda_peak_stream_read over 2 GiB; meda_peak_mfma_bf16, 65536 32x32x16 instructions per wave, "
+                   "2 waves per SIMD; median of 5 launches"}
+
+
+def _cpu_info():
+    model = ""
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    return model, int(threads)
+
+
+def cpu_baseline(wl, budgets, seconds_target=20.0):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload.
+
+    Small workloads (the whole pass fits the time box): the oracle's whole pass on the first n layers, budget
+    scaled to n layers, scaled by L/n.  Large workloads: the scoring of one layer and the selection / matching /
+    merging of heads of the layer with the smallest and of the layer with the largest budget (the two ends of
+    the per-head cost, which grows with the similarity flops 2 (T - S) S d); the pass is extrapolated as
+    L * t_score + Hkv * sum_l (a + b * flops_l) with a, b from those two measurements.  The layer budgets S_l of
+    the sampled layers are this run's (timing only: no parity statement rests on this number)."""
     import numpy as np
     from oracle import meda_oracle as O
     from workloads import generate, variant
     from workloads.gen import to_float64
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = 1
+    model, threads = _cpu_info()
+    base = {"unit": "tokens/s", "cores": threads, "host_cpus": os.cpu_count(), "cpu_model": model, "kind": "oracle"}
+    L, Hkv, T, d, W = wl.n_layers, wl.n_kv_heads, wl.seq_len, wl.head_dim, wl.window
 
-    def run(n_layers):
-        sub = variant(wl, n_layers=n_layers, total_budget=(wl.total_budget * n_layers) // wl.n_layers)
+    def whole(n_layers):
+        sub = variant(wl, n_layers=n_layers, total_budget=(wl.total_budget * n_layers) // L)
         data = generate(sub, threads=min(8, n_layers))
         q, k, v = to_float64(data["q"]), to_float64(data["k"]), to_float64(data["v"])
         t0 = time.perf_counter()
@@ -136,13 +269,50 @@ def cpu_baseline(wl, seconds_target=20.0):
                         recent_num=sub.recent_num, recent_den=sub.recent_den)
         return time.perf_counter() - t0
 
-    t1 = run(1)
-    n = int(max(1, min(wl.n_layers, seconds_target // max(t1, 1e-3))))
-    t = run(n) if n > 1 else t1
-    per_pass = t * wl.n_layers / n
-    return {"value": wl.seq_len / per_pass, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"first {n} of {wl.n_layers} layers (all heads, budget scaled to {n} layers), "
-                      f"{t:.1f} s, scaled by {wl.n_layers}/{n}"}
+    flops = [2.0 * (T - s) * s * d for s in budgets]            # per head
+    if sum(flops) * Hkv < 2e11:                                  # small: time whole layers
+        t1 = whole(1)
+        n = int(max(1, min(L, seconds_target // max(t1, 1e-3))))
+        t = whole(n) if n > 1 else t1
+        per_pass = t * L / n
+        return {**base, "value": T / per_pass,
+                "sample": f"first {n} of {L} layers (all heads, budget scaled to {n} layers), {t:.1f} s, "
+                          f"scaled by {L}/{n}"}
+
+    l_lo, l_hi = int(np.argmin(budgets)), int(np.argmax(budgets))
+    mask = generate(variant(wl, n_layers=1), layers=[0])["mask"].numpy()
+
+    def sample_layer(l, score, max_heads, box):
+        data = generate(wl, layers=[l], threads=1)
+        q, k, v = to_float64(data["q"][0]), to_float64(data["k"][0]), to_float64(data["v"][0])
+        t_score = None
+        t0 = time.perf_counter()
+        a_s, _ = O.layer_scores_and_entropy(q, k, mask)
+        if score:
+            t_score = time.perf_counter() - t0
+        s = int(budgets[l])
+        m = max(min(W, s), (s * wl.recent_num) // wl.recent_den)
+        heads, t_heads = 0, 0.0
+        while heads < max_heads and (heads == 0 or t_heads * (heads + 1) / heads < box):
+            t0 = time.perf_counter()
+            O.compress_layer_head(k[heads], v[heads], a_s[heads], mask, s - m, m, wl.dtype)
+            t_heads += time.perf_counter() - t0
+            heads += 1
+        return t_score, t_heads / heads, heads
+
+    t_score, t_lo, h_lo = sample_layer(l_lo, True, Hkv, 0.25 * seconds_target)
+    _, t_hi, h_hi = sample_layer(l_hi, False, Hkv, 0.5 * seconds_target)
+    if flops[l_hi] > flops[l_lo]:
+        b = (t_hi - t_lo) / (flops[l_hi] - flops[l_lo])
+        a = t_lo - b * flops[l_lo]
+    else:
+        a, b = 0.0, t_hi / max(flops[l_hi], 1.0)
+    per_pass = L * t_score + Hkv * sum(a + b * f for f in flops)
+    return {**base, "value": T / per_pass, "extrapolated": True,
+            "sample": f"scoring of layer {l_lo} ({t_score:.1f} s, all heads); selection, matching and merging of "
+                      f"{h_lo} head(s) of layer {l_lo} (S={budgets[l_lo]}, {t_lo:.2f} s/head) and {h_hi} head(s) of "
+                      f"layer {l_hi} (S={budgets[l_hi]}, {t_hi:.2f} s/head); pass = {L} x scoring + {Hkv} heads x "
+                      f"sum over layers of a + b x 2(T-S)S d flops, a, b from the two layers: {per_pass:.0f} s"}
 
 
 def main():
@@ -150,8 +320,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="llava7b_multi_image")
+    ap.add_argument("--workload", default=HEADLINE)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-workload", action="store_true", help="skip the short runs of the other configurations")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the read-stream and matrix-instruction micro-kernels")
     ap.add_argument("--full-prompt", action="store_true",
                     help="score with every prompt position instead of the observation window")
     ap.add_argument("--no-decode", action="store_true", help="skip the decoding-step measurement")
@@ -181,96 +353,53 @@ def main():
 
     import torch
     import paper_2502_17599_amd as pkg
-    from workloads import generate, get_workload
+    from workloads import get_workload
+    from workloads.configs import ORDER
 
     wl = get_workload(args.workload)
     flags = 0
-    if args.full_prompt:       # every prompt position scores the keys (the three scoring kernels are timed as one)
+    if args.full_prompt:       # every prompt position scores the keys
         from workloads import variant
         wl = variant(wl, score_rows=wl.seq_len)
         flags = pkg.FLAG_FULL_PROMPT
-        PHASE_BOUND["score_stats"] = "mfma"
-        PHASE_KERNELS["score_stats"] = ["score_stats_kernel", "stats_combine_kernel", "score_accum_kernel"]
     dev = torch.device("cuda:0")
     n_seqs = max(args.batch, 0)
-    if n_seqs:
-        from workloads import generate_batch, variant
-        data = generate_batch([variant(wl, seed=wl.seed + i) for i in range(n_seqs)], threads=16)
-    else:
-        data = generate(wl, threads=16)
-    q, k, v, mask = (data[n].to(dev) for n in ("q", "k", "v", "mask"))
-    params = pkg.make_params(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.seq_len, wl.window,
-                             wl.total_budget, q.dtype, wl.recent_num, wl.recent_den, 0.0, flags, n_seqs)
-    comp = pkg.Compressor(params, dev, want_entropy=True, want_sel_idx=True, want_merge_assign=False)
-    stream = torch.cuda.current_stream(dev)
+    plain = not (args.full_prompt or n_seqs)
 
-    names = [pkg.meda_phase_name(i) for i in range(pkg.N_PHASES)]
-    # warm-up with every kernel bracketed by events: gives the per-phase times and names the dominant kernel
-    comp(q, k, v, mask, stream)            # first call loads the code objects: not part of any figure
-    torch.cuda.synchronize()
-    pkg.meda_profile_enable(True)
-    pkg.meda_profile_read(reset=True)
-    for _ in range(max(args.warmup, 1)):
-        comp(q, k, v, mask, stream)
-    torch.cuda.synchronize()
-    warm_ms, warm_calls = pkg.meda_profile_read(reset=True)
-    per_phase = {n: warm_ms[i] / warm_calls for i, n in enumerate(names)}
-    dom = max(names, key=lambda n: per_phase[n])
-    # timed region: only the dominant kernel is bracketed (two events per call), on the stream it is launched on
-    events = not args.no_phase_events
-    pkg.meda_profile_enable(events, names.index(dom))
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        out = comp(q, k, v, mask, stream)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    phase_ms, n_calls = pkg.meda_profile_read(reset=True)
-    pkg.meda_profile_enable(False)
-    dom_ms = phase_ms[names.index(dom)] / n_calls if n_calls else None
-
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    seqs = max(n_seqs, 1)
-    budgets = out.layer_len.cpu().reshape(seqs, wl.n_layers).tolist()
-    work = {}
-    for b in budgets:          # the sequences of a batch are independent: their work adds up
-        for key, val in algorithmic_work(wl, b).items():
-            work[key] = work.get(key, 0) + val
-
-    roofline = None
-    if dom_ms:
-        bound = PHASE_BOUND[dom]
-        t_s = dom_ms * 1e-3
-        if bound == "mfma":
-            achieved, peak, unit = work[dom] / t_s / 1e12, MFMA_PEAK_TFLOPS[wl.dtype], "TFLOP/s"
-        else:
-            achieved, peak, unit = work[dom] / t_s / 1e9, HBM_PEAK_GBS, "GB/s"
-        roofline = {"kernel": dom, "launches": PHASE_KERNELS[dom], "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                    "frac": achieved / peak,
-                    "traffic": None if (args.full_prompt or n_seqs) else measured_traffic(wl.name, dom),
-                    "kernel_ms": dom_ms, "launches_timed": n_calls}
-
-    e = 2 if wl.dtype == "bf16" else 4
-    alg_bytes = work["merge_write"]        # K and V once + the output: the traffic of the whole pass
+    head, kept = time_pass(pkg, torch, wl, dev, args.steps, args.warmup, flags, n_seqs,
+                           phase_events=not args.no_phase_events, keep=True)
+    q, k, v, out, budgets = kept
     rec = {
-        "metric": "kv_tokens_compressed_per_sec", "value": seqs * wl.seq_len / (ms_per_step * 1e-3), "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
+        "metric": "kv_tokens_compressed_per_sec", "value": head["value"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": head["dtype"],
         "data": "synthetic",
-        "config": {"workload": wl.name + ("+full_prompt_scoring" if args.full_prompt else ""), "layers": wl.n_layers, "q_heads": wl.n_q_heads, "kv_heads": wl.n_kv_heads,
-                   "head_dim": wl.head_dim, "seq_len": wl.seq_len, "window": wl.window,
-                   "total_budget": wl.total_budget, "seed": wl.seed, "batch": seqs},
-        "kv_rows_per_sec": seqs * wl.n_layers * wl.n_kv_heads * wl.seq_len / (ms_per_step * 1e-3),
-        "pass_hbm_frac": (alg_bytes / (ms_per_step * 1e-3)) / (HBM_PEAK_GBS * 1e9),
-        "pass_mfma_frac": ((work["similarity"] + 2.0 * seqs * wl.n_layers * wl.n_q_heads * wl.window * wl.seq_len * wl.head_dim)
-                           / (ms_per_step * 1e-3)) / (MFMA_PEAK_TFLOPS[wl.dtype] * 1e12),
-        "phase_ms_warmup": per_phase,
-        "roofline": roofline,
     }
+    rec.update({key: val for key, val in head.items() if key not in rec})
+    rec["layer_budgets"] = budgets
     if not args.no_decode and not n_seqs:
         rec["decode_step"] = decode_step_record(pkg, torch, wl, out, q.dtype, k, v, dev)
+    del q, k, v, out, kept
+    torch.cuda.empty_cache()
+    if plain and not args.no_per_workload:
+        # short runs of the other configurations (parity-test cases; context for the headline)
+        others = []
+        for name in ORDER:
+            if name == wl.name:
+                continue
+            o, _ = time_pass(pkg, torch, get_workload(name), dev, steps=10, warmup=2)
+            torch.cuda.empty_cache()
+            others.append({"workload": name, "ms_per_step": o["ms_per_step"],
+                           "ms_per_step_event_median": o["ms_per_step_event_median"], "tokens_per_s": o["value"],
+                           "dtype": o["dtype"], "pass_hbm_frac": o["pass_hbm_frac"], "pass_mfma_frac": o["pass_mfma_frac"],
+                           "dominant_kernel": o["roofline"]["kernel"], "dominant_bound": o["roofline"]["bound"],
+                           "dominant_kernel_ms": o["roofline"]["kernel_ms"], "dominant_frac": o["roofline"]["frac"],
+                           "phase_ms_warmup": o["phase_ms_warmup"]})
+        rec["per_workload"] = others
+    if not args.no_peaks:
+        rec["measured_peak"] = measured_peaks(pkg, torch, dev)
     if not args.no_cpu_baseline and not n_seqs:
-        rec["cpu_baseline"] = cpu_baseline(wl)
+        rec["cpu_baseline"] = cpu_baseline(wl, budgets)
     print(json.dumps(rec))
 
 

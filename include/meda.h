@@ -227,6 +227,21 @@ meda_status meda_decode_attention_fp8(const meda_decode_params* params, const vo
                                       const void* v_new, void* out, void* workspace, size_t workspace_bytes,
                                       void* hip_stream);
 
+/*
+ * Measurement aids for the benchmark: what this GPU delivers to the simplest kernel of each of the two kinds the
+ * pass is made of.  Both only enqueue one kernel on hip_stream; the caller times them (events on that stream).
+ *   meda_peak_stream_read   reads `bytes` bytes (multiple of 16 used; src device pointer, 16-byte aligned) once,
+ *                           with 16-byte streaming loads, eight in flight per lane; nothing is written.
+ *                           Rate = bytes / time: the HBM read rate a kernel of the scoring / merge kind can reach.
+ *   meda_peak_mfma_bf16     every SIMD of the chip issues `mfma_per_wave` (rounded down to a multiple of 16,
+ *                           >= 16) bf16 32x32x16 matrix instructions from registers, two waves per SIMD, four
+ *                           independent accumulator chains per wave; *total_mfma (host pointer) receives the
+ *                           number issued over the whole chip.  Rate = total_mfma * 32768 flop / time.
+ * `sink` is a 4-byte aligned device word that is never actually written (it keeps the work alive).
+ */
+meda_status meda_peak_stream_read(const void* src, size_t bytes, void* sink, void* hip_stream);
+meda_status meda_peak_mfma_bf16(int64_t mfma_per_wave, int64_t* total_mfma, void* sink, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -15,7 +15,7 @@ EXPORTED_SYMBOLS = ("meda_workspace_bytes", "meda_compress", "meda_workspace_reg
                     "meda_profile_enable", "meda_profile_read", "meda_phase_name", "meda_status_string",
                     "meda_decode_workspace_bytes", "meda_decode_attention",
                     "meda_quantize_fp8", "meda_dequantize_fp8", "meda_decode_attention_fp8",
-                    "meda_decode_attention_noalloc")
+                    "meda_decode_attention_noalloc", "meda_peak_stream_read", "meda_peak_mfma_bf16")
 DECODE_NOALLOC_MAX_BYTES = 40 << 20
 REGIONS = {"col_scores": 0, "inv_norm": 1, "row_stats": 2, "alloc": 3, "less_idx": 4, "less_slot": 5}
 N_PHASES = 8
@@ -86,6 +86,10 @@ def load_library() -> ctypes.CDLL:
     lib.meda_decode_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.meda_decode_attention_noalloc.restype = ctypes.c_int
     lib.meda_decode_attention_noalloc.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.meda_peak_stream_read.restype = ctypes.c_int
+    lib.meda_peak_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.meda_peak_mfma_bf16.restype = ctypes.c_int
+    lib.meda_peak_mfma_bf16.argtypes = [ctypes.c_int64, ctypes.POINTER(ctypes.c_int64), vp, vp]
     lib.meda_quantize_fp8.restype = ctypes.c_int
     lib.meda_quantize_fp8.argtypes = [vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, vp, vp, vp]
     lib.meda_dequantize_fp8.restype = ctypes.c_int
@@ -303,6 +307,22 @@ def meda_decode_attention_noalloc(params: MedaDecodeParams, q, k_cache, v_cache,
         ctypes.byref(params), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(layer_len), _ptr(layer_off),
         _ptr(k_new), _ptr(v_new), _ptr(out), ctypes.c_void_p(stream.cuda_stream)))
     return out
+
+
+def meda_peak_stream_read(buf: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    """Enqueue one streaming read of ``buf`` (measurement aid; ``sink`` is a 4-byte device word)."""
+    stream = stream if stream is not None else torch.cuda.current_stream(buf.device)
+    _check(load_library().meda_peak_stream_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink),
+                                                ctypes.c_void_p(stream.cuda_stream)))
+
+
+def meda_peak_mfma_bf16(mfma_per_wave: int, sink: torch.Tensor, stream=None) -> int:
+    """Enqueue the matrix-instruction micro-kernel (measurement aid); returns the instructions issued chip-wide."""
+    stream = stream if stream is not None else torch.cuda.current_stream(sink.device)
+    total = ctypes.c_int64(0)
+    _check(load_library().meda_peak_mfma_bf16(int(mfma_per_wave), ctypes.byref(total), _ptr(sink),
+                                              ctypes.c_void_p(stream.cuda_stream)))
+    return int(total.value)
 
 
 def meda_quantize_fp8(rows: torch.Tensor, stream=None):

@@ -63,16 +63,53 @@ def gpu_head(wl, gpu, l, g):
     return gpu["sel_idx"][a:a + S], gpu["k_out"][a:a + S], gpu["v_out"][a:a + S]
 
 
-def oracle_scores(wl, data, layers=None):
-    """Oracle column scores and entropies for the given layers (all by default)."""
+def oracle_scores(wl, data, layers=None, threads=1):
+    """Oracle column scores and entropies for the given layers (all by default).  ``threads`` > 1 runs that many
+    layers side by side (numpy releases the interpreter lock inside its loops); the result does not depend on it."""
     q = data["q"]; k = data["k"]; mask = data["mask"].numpy()
-    layers = range(wl.n_layers) if layers is None else layers
-    a_s, ent = {}, {}
-    for l in layers:
-        a_l, e_l = O.layer_scores_and_entropy(to_float64(q[l]), to_float64(k[l]), mask)
-        a_s[l] = a_l
-        ent[l] = e_l
+    layers = list(range(wl.n_layers) if layers is None else layers)
+
+    def one(l):
+        return O.layer_scores_and_entropy(to_float64(q[l]), to_float64(k[l]), mask)
+
+    if threads > 1 and len(layers) > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=threads) as pool:
+            results = list(pool.map(one, layers))
+    else:
+        results = [one(l) for l in layers]
+    a_s = {l: r[0] for l, r in zip(layers, results)}
+    ent = {l: r[1] for l, r in zip(layers, results)}
     return a_s, ent
+
+
+def budget_margins(wl, e_ref):
+    """How far every layer's budget is from being rounded the other way.
+
+    The integer budgets are floor(x_l) plus one for the layers with the largest fractional parts (largest
+    remainder).  A layer that got the extra slot loses it when its fractional part falls below the best one that
+    did not get it; a layer that did not get it gains it when its fractional part rises above the worst one that
+    did.  Returns (margin in slots, relative entropy change that would move x_l by that margin) per layer; layers
+    pinned at the floor or the cap have an infinite margin unless their clamp is about to release.  With x_l
+    proportional to exp(E_l), dx_l = x_l dE_l (the shift of the water level by one layer's change is second order)."""
+    lo, hi = min(wl.window, wl.seq_len), wl.seq_len
+    x = O.allocation_reals(np.asarray(e_ref, dtype=np.float64), wl.total_budget, lo, hi)
+    fl = np.floor(x)
+    frac = x - fl
+    S, _, _, _ = O.allocate_budgets(np.asarray(e_ref, dtype=np.float64), wl.total_budget, wl.seq_len, wl.window,
+                                    wl.recent_num, wl.recent_den)
+    got = (S - fl.astype(np.int64)) > 0
+    free = (x > lo) & (x < hi)
+    margin = np.full(len(x), np.inf)
+    if got.any() and (~got & free).any():
+        best_without = frac[~got & free].max()
+        worst_with = frac[got].min()
+        margin[got] = frac[got] - best_without
+        sel = ~got & free
+        margin[sel] = worst_with - frac[sel]
+    margin = np.where(free, margin, np.inf)
+    rel_entropy = margin / np.maximum(x, 1.0) / np.maximum(np.abs(e_ref), 1e-30)
+    return margin, rel_entropy
 
 
 def check_budgets(wl, gpu, ent_oracle):
@@ -146,13 +183,14 @@ def _unit(x):
     return x / np.maximum(np.linalg.norm(x, axis=1, keepdims=True), 1e-30)
 
 
-def check_all(wl, data, gpu, heads=None, score_layers=None, verbose=True):
-    """Full comparison.  ``heads``: iterable of (layer, head) to check downstream of the scores (all by default).
+def check_all(wl, data, gpu, heads=None, score_layers=None, verbose=True, threads=1):
+    """Full comparison.  ``heads``: iterable of (layer, head) to check downstream of the scores (all by default),
+    or a function of the validated budgets S returning them.
     ``score_layers``: layers whose scores/entropies are compared (all by default; budgets need all)."""
     L, Hkv = wl.n_layers, wl.n_kv_heads
     stats = {"heads": 0, "rows": 0, "ambiguous_rows": 0, "sets_differing_in_tie_band": 0,
-             "max_kv_err": 0.0, "kv_elems_not_bit_exact": 0}
-    a_s, ent = oracle_scores(wl, data, score_layers)
+             "max_kv_err": 0.0, "kv_elems_not_bit_exact": 0, "layers_passing_only_by_entropy_floor": 0}
+    a_s, ent = oracle_scores(wl, data, score_layers, threads)
     k = data["k"]
     for l in a_s:
         ref = a_s[l]
@@ -165,10 +203,24 @@ def check_all(wl, data, gpu, heads=None, score_layers=None, verbose=True):
         # probabilities (1 - 2^-24): their absolute error of order 1e-8 moves no budget (S_l ~ exp(E))
         assert abs(gpu["entropy"][l] - e_ref) <= 1e-3 * abs(e_ref) + 1e-7, \
             f"layer {l}: entropy {gpu['entropy'][l]} vs {e_ref}"
+        if abs(gpu["entropy"][l] - e_ref) > 1e-3 * abs(e_ref):
+            stats["layers_passing_only_by_entropy_floor"] += 1
     stats["max_entropy_rel_err"] = max(abs(gpu["entropy"][l] - ent[l][2]) / max(abs(ent[l][2]), 1e-30) for l in ent)
     if len(ent) == L:
         (S, M, N, off), strict = check_budgets(wl, gpu, ent)
         stats["budgets_strictly_equal"] = strict
+        # how close every layer is to being rounded the other way, against the entropy error actually observed
+        e_vec = np.array([ent[l][2] for l in range(L)])
+        margin, rel = budget_margins(wl, e_vec)
+        err_rel = np.abs(gpu["entropy"] - e_vec) / np.maximum(np.abs(e_vec), 1e-30)
+        stats["min_budget_margin_slots"] = float(margin.min())
+        stats["min_rel_entropy_change_flipping_a_budget"] = float(rel.min())
+        if verbose:
+            print(f"[parity {wl.name}] budgets {S.tolist()}", flush=True)
+            print(f"[parity {wl.name}] margin to the nearest rounding boundary, slots per layer: "
+                  + " ".join("inf" if not np.isfinite(m) else f"{m:.3f}" for m in margin), flush=True)
+            print(f"[parity {wl.name}] relative entropy change that would flip a budget: min {rel.min():.2e}; "
+                  f"observed relative entropy error: max {err_rel.max():.2e}", flush=True)
     else:
         # Only some layers were scored by the oracle (very large workloads): the budgets cannot be derived
         # from oracle entropies alone.  What can be checked: the entropies of the sampled layers (above),
@@ -180,6 +232,8 @@ def check_all(wl, data, gpu, heads=None, score_layers=None, verbose=True):
         assert np.array_equal(gpu["alloc"][:, 1], M) and np.array_equal(gpu["alloc"][:, 2], N)
         assert np.array_equal(np.diff(gpu["off"]), gpu["S"])
         stats["budgets_strictly_equal"] = None
+    if callable(heads):
+        heads = heads(S)
     pairs = [(l, g) for l in range(L) for g in range(Hkv)] if heads is None else list(heads)
     for l, g in pairs:
         check_head(wl, data, gpu, a_s[l], l, g, int(N[l]), int(M[l]), stats)

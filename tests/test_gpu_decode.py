@@ -108,3 +108,15 @@ def test_decode_full_budget_is_attention_over_the_original_cache():
 def test_decode_llava7b_full_size_sampled_layers():
     wl = get_workload("llava7b_multi_image")
     _check(wl, n_new=17, layers=[0, 13, wl.n_layers - 1])
+
+
+def test_decode_long_video_full_size_sampled_layers():
+    # 7 query heads per kv head (padded to 8 in the kernel), 37376 positions, ragged budgets of the full-size pass
+    wl = get_workload("long_video")
+    _check(wl, n_new=5, layers=[0, 13, wl.n_layers - 1])
+
+
+def test_decode_long_multi_image_full_size_sampled_layers():
+    # 4 query heads per kv head at full size
+    wl = get_workload("long_multi_image")
+    _check(wl, n_new=0, layers=[1, wl.n_layers - 2])

@@ -68,3 +68,16 @@ def test_full_prompt_mid_size_bf16_one_head_per_kv_head():
     wl = variant(TINY, name="fp_mid", n_layers=4, n_q_heads=8, n_kv_heads=8, head_dim=128, dtype="bf16",
                  layout=layout, window=32, total_budget=4 * 400, seed=21, score_rows=2048)
     _case(wl, heads=[(l, g) for l in range(4) for g in (0, 5)])
+
+
+def test_full_prompt_llava7b_shape_two_layers():
+    # the shape the full-prompt mode is benchmarked on (32 heads without grouping, 4096 positions, 32 row blocks),
+    # two layers with different temperatures; the oracle takes a few minutes for them, run side by side
+    base = get_workload("llava7b_multi_image")
+    wl = variant(base, name="fp_llava7b_2_layers", n_layers=2, total_budget=2 * 512, score_rows=base.seq_len)
+    print(f"\n[full-prompt case] {wl.name}: L={wl.n_layers} Hq={wl.n_q_heads} Hkv={wl.n_kv_heads} d={wl.head_dim} "
+          f"T={wl.seq_len} W={wl.window} B={wl.total_budget} {wl.dtype}", flush=True)
+    data = generate(wl)
+    comp, gpu = run_gpu(wl, data)
+    stats = check_all(wl, data, gpu, heads=[(0, 0), (0, 17), (1, 31)], threads=2)
+    assert stats["layers_passing_only_by_entropy_floor"] == 0

@@ -23,33 +23,40 @@ def test_llava7b_multi_image_full_size():
     print(f"\n[case] {wl.name} T={wl.seq_len} B={wl.total_budget}", flush=True)
     data = generate(wl, threads=16)
     comp, gpu = run_gpu(wl, data)
-    stats = check_all(wl, data, gpu, heads=_sample_heads(wl, 24))
+    stats = check_all(wl, data, gpu, heads=_sample_heads(wl, 24), threads=4)
     assert stats["ambiguous_rows"] <= 1e-3 * max(stats["rows"], 1)
+    assert stats["layers_passing_only_by_entropy_floor"] == 0
 
 
-def _full_size(name, n_heads, score_layers=None):
+def _full_size(name, n_heads, threads=1, extremes=False):
     wl = get_workload(name)
     print(f"\n[case] {wl.name} T={wl.seq_len} B={wl.total_budget}", flush=True)
     data = generate(wl, threads=16)
     comp, gpu = run_gpu(wl, data)
-    heads = _sample_heads(wl, n_heads)
-    if score_layers is not None:
-        heads = [(l, g) for l, g in heads if l in score_layers]
-    stats = check_all(wl, data, gpu, heads=heads, score_layers=score_layers)
+
+    def heads(S):
+        pairs = _sample_heads(wl, n_heads)
+        if extremes:   # the layers with the largest and the smallest budget (cap / floor of the allocation active)
+            pairs = sorted(set(pairs) | {(int(np.argmax(S)), 0), (int(np.argmin(S)), wl.n_kv_heads - 1)})
+        return pairs
+
+    stats = check_all(wl, data, gpu, heads=heads, threads=threads)
     assert stats["ambiguous_rows"] <= 1e-3 * max(stats["rows"], 1)
+    assert stats["layers_passing_only_by_entropy_floor"] == 0
     return stats
 
 
 def test_long_multi_image_full_size():
-    _full_size("long_multi_image", 6)
+    _full_size("long_multi_image", 6, threads=4, extremes=True)
 
 
 def test_long_video_full_size():
-    _full_size("long_video", 4)
+    _full_size("long_video", 4, threads=4, extremes=True)
 
 
-def test_extreme_full_size_sampled_layers():
-    # 131072 positions: the oracle scores two layers (first and last); selection, matching and merging are
-    # checked for one head of each against the oracle run with the budgets validated in check_all
-    wl = get_workload("extreme")
-    _full_size("extreme", 2, score_layers=[0, wl.n_layers - 1])
+def test_extreme_full_size_all_layers():
+    # 131072 positions: the oracle scores every layer (four side by side), so all 32 entropies and budgets are
+    # compared; selection, matching and merging of ten (layer, head) pairs, among them the layer with the largest
+    # and the one with the smallest budget
+    stats = _full_size("extreme", 8, threads=4, extremes=True)
+    assert stats["budgets_strictly_equal"]

@@ -136,3 +136,25 @@ def test_kv_memory_formula_golden():
     # the full-cache figure printed in the latency/memory table corresponds to a whole number of tokens
     tokens = vals["full_cache_gib"] * 1024 ** 3 / per_token
     assert abs(tokens - round(tokens)) < 0.5 and 4900 < tokens < 5000
+
+
+def test_budget_margins_predict_which_perturbation_flips_a_budget():
+    """The margin report of the parity helper: shifting one layer's entropy by clearly less than its reported
+    relative margin leaves every budget as it is, shifting it by clearly more changes some budget."""
+    from parity import budget_margins
+    from workloads import get_workload, variant
+    wl = variant(get_workload("tiny"), n_layers=6, total_budget=6 * 300)
+    rng = np.random.default_rng(3)
+    e = rng.uniform(3.0, 5.0, size=6)
+    S0 = O.allocate_budgets(e, wl.total_budget, wl.seq_len, wl.window)[0]
+    margin, rel = budget_margins(wl, e)
+    assert np.all(margin > 0) and np.isfinite(margin).all()
+    l = int(np.argmin(rel))
+    for sign in (+1.0, -1.0):
+        small = e.copy(); small[l] *= 1.0 + sign * 0.2 * rel[l]
+        assert np.array_equal(O.allocate_budgets(small, wl.total_budget, wl.seq_len, wl.window)[0], S0)
+    flipped = False
+    for sign in (+1.0, -1.0):
+        big = e.copy(); big[l] *= 1.0 + sign * 5.0 * rel[l]
+        flipped |= not np.array_equal(O.allocate_budgets(big, wl.total_budget, wl.seq_len, wl.window)[0], S0)
+    assert flipped
