@@ -69,8 +69,13 @@ def oracle_scores(wl, data, layers=None, threads=1):
     q = data["q"]; k = data["k"]; mask = data["mask"].numpy()
     layers = list(range(wl.n_layers) if layers is None else layers)
 
+    slow = q.shape[1] * q.shape[2] * k.shape[2] >= (1 << 26)   # a layer takes seconds: say that it is alive
+
     def one(l):
-        return O.layer_scores_and_entropy(to_float64(q[l]), to_float64(k[l]), mask)
+        r = O.layer_scores_and_entropy(to_float64(q[l]), to_float64(k[l]), mask)
+        if slow:
+            print(f"[oracle {wl.name}] layer {l} scored", flush=True)
+        return r
 
     if threads > 1 and len(layers) > 1:
         from concurrent.futures import ThreadPoolExecutor
