@@ -110,7 +110,8 @@ def cross_modal_probs(s: np.ndarray, mask: np.ndarray) -> np.ndarray:
     mask[T-W+i]) attends, in the cross-modal matrix, only to the visible keys of the *other*
     modality, and the softmax is taken over that sub-block (Section 3.2: A_TV is the softmax
     of Q_T K_V^T, A_VT the softmax of Q_V K_T^T).  The per-head matrices are averaged over
-    the heads before the entropy ("A is average attention across multi-heads").
+    the heads before the entropy (Section 3.2, definition of E(A): the matrix whose entropy is
+    taken is the head average).
     Returns pbar [W, T]; entries outside a row's cross-modal set are 0.
     """
     Hq, W, T = s.shape

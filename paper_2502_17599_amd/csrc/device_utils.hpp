@@ -119,6 +119,23 @@ __device__ __forceinline__ void store16_stream(void* p, const uint4& v) {
   __builtin_nontemporal_store(t, reinterpret_cast<u32x4_t*>(p));
 }
 
+// 16 (or 4) bytes per lane from global memory straight into LDS, without passing through registers: lane i's
+// piece, read at gbase + goff (gbase the same for every lane of the wave, goff this lane's byte offset),
+// lands at LDS byte address lds_base + 16 i (4 i), lds_base being the same for every lane.  The copy is
+// asynchronous and counted like a global load; the compiler does not know that it writes LDS, so the wave that
+// issued copies waits for them itself with async_copy_wait<N>() (returns when at most N of its copies, the
+// youngest ones, are still in flight) and a barrier after that wait publishes them to the other waves.
+__device__ __forceinline__ void async_copy16_to_lds(const void* gbase, unsigned goff, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(goff), "s"(gbase), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ void async_copy4_to_lds(const void* gbase, unsigned goff, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(goff), "s"(gbase), "s"(lds_base) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void async_copy_wait() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 // Copy `rows` consecutive rows (contiguous in global memory) into a padded LDS tile; rows at or
 // beyond `rows_valid` are zero-filled.
 template <typename T, int D>

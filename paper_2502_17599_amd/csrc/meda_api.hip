@@ -106,6 +106,7 @@ meda_status make_plan(const meda_params* p, Plan* out) {
   pl.off_layer_off = take((size_t)(pl.L + 1) * 8);
   pl.off_sel_idx = take((size_t)pl.B * pl.Hkv * 4);
   pl.off_sel_inv = take((size_t)pl.B * pl.Hkv * 4);
+  pl.off_packed_k = take((size_t)pl.B * pl.Hkv * pl.d * pl.elt);
   const size_t less_bytes = pl.n_less_total * 4 + 16;
   pl.off_less_idx = take(less_bytes);
   pl.off_less_slot = take(less_bytes);

@@ -17,6 +17,7 @@ struct MergeArgs {
   const int64_t* off;       // [L+1]
   const int32_t* sel_idx;   // ragged [B*Hkv]: row id (l*Hkv+g)*T + position of every conserved key
   const float* sel_inv_norm;  // ragged: 1/|k| of the conserved keys
+  char* packed_k;           // ragged [B*Hkv][d]: the conserved keys, copied once so that tiles of them are contiguous
   const int32_t* less_idx;  // ragged: row ids of the less-important keys (ascending)
   int32_t* less_slot;       // ragged: slot each of them merges into
   int32_t* sort_key[2];     // ping-pong buffers of the segment sort
@@ -57,17 +58,15 @@ constexpr int resident_capacity() {
   return Tile<T, D>::kRowBytes > 256 ? 0 : kResLdsBytes / (Tile<T, D>::kStride + 4) / 32 * 32;
 }
 
-// grid (ceil(T / 256), Hkv, L); 4 waves x 64 less-important rows.  u_ij = (k_i . k_j)/(|k_i| |k_j|):
-// the raw keys are multiplied (bf16 products are exact in the fp32 accumulator), the factor 1/|k_j|
-// of the conserved key is applied to the accumulator, and the positive factor 1/|k_i| of the row is
-// dropped because it cannot change the argmax over j.  Ties go to the lower slot.
+// u_ij = (k_i . k_j)/(|k_i| |k_j|): the raw keys are multiplied (bf16 products are exact in the fp32
+// accumulator), the factor 1/|k_j| of the conserved key is applied to the accumulator, and the positive
+// factor 1/|k_i| of the row is dropped because it cannot change the argmax over j.  Ties go to the lower slot.
 //
-// Each wave keeps its 64 rows as two B-operand fragments in registers for the whole kernel and
-// streams the conserved keys of its (layer, head) through LDS as A operands, in tiles of 64 slots
-// (double buffered: the global loads of tile t+1 and the position loads of tile t+2 are in flight
-// while tile t is multiplied).  With the conserved keys as operand A, a lane owns ONE row and sees
-// 16 candidate slots per 32x32 block in its 16 accumulator registers: the running best of the row is
-// one value per lane and the block maximum is a max3 tree (see RowBest).
+// A wave keeps 64 less-important rows as two B-operand fragments in registers and takes the conserved keys of
+// its (layer, head) from LDS as A operands, 32 slots (one block) at a time.  With the conserved keys as
+// operand A, a lane owns ONE row and sees 16 candidate slots per block in its 16 accumulator registers: the
+// running best of the row is one value per lane and the block maximum is a max3 tree.
+//
 // Running best of one row (one lane) over the blocks it has seen: the best value, the first slot of
 // the block that produced it and that block's 16 scaled products.  Keeping the products postpones the
 // search for the winning register to the end of the kernel: per block only the maximum is formed
@@ -78,14 +77,37 @@ struct RowBest {
   float u[16];
 };
 
-__device__ __forceinline__ void argmax_block(const f32x16_t& acc, const float (&iv)[16], int slot0, RowBest& rb) {
-  float u[16];
+__device__ __forceinline__ void row_best_init(RowBest& rb) {
+  rb.best = -INFINITY;
+  rb.slot0 = 0;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) u[r] = acc[r] * iv[r];
-  float bm = fmaxf(fmaxf(u[0], u[1]), u[2]);
+  for (int r = 0; r < 16; ++r) rb.u[r] = -INFINITY;
+}
+
+// The 1/|k_j| of this lane's 16 slots of a block (iv_lds points at the block's entries of this lane group: slot
+// r4*8 + i of the group sits at iv_lds[r4*8 + i]).
+__device__ __forceinline__ void load_inv(float (&iv)[16], const float* iv_lds) {
 #pragma unroll
-  for (int r = 3; r < 15; r += 2) bm = fmaxf(fmaxf(bm, u[r]), u[r + 1]);
-  bm = fmaxf(bm, u[15]);
+  for (int r4 = 0; r4 < 4; ++r4) {
+    const float4 v = *reinterpret_cast<const float4*>(iv_lds + r4 * 8);
+    iv[r4 * 4 + 0] = v.x;
+    iv[r4 * 4 + 1] = v.y;
+    iv[r4 * 4 + 2] = v.z;
+    iv[r4 * 4 + 3] = v.w;
+  }
+}
+
+// Scales the 16 products of this lane by the 1/|k_j| of their slots and returns their maximum.
+__device__ __forceinline__ float scale_max(f32x16_t& p, const float (&iv)[16]) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) p[r] *= iv[r];
+  float bm = fmaxf(fmaxf(p[0], p[1]), p[2]);
+#pragma unroll
+  for (int r = 3; r < 15; r += 2) bm = fmaxf(fmaxf(bm, p[r]), p[r + 1]);
+  return fmaxf(bm, p[15]);
+}
+
+__device__ __forceinline__ void keep_if_improved(const f32x16_t& u, float bm, int slot0, RowBest& rb) {
   const bool improved = bm > rb.best;  // strict: an equal value in a later block does not replace
   if (__ballot(improved) != 0ull) {
 #pragma unroll
@@ -106,45 +128,89 @@ __device__ __forceinline__ int row_best_slot(const RowBest& rb, int kg) {
   return rb.slot0 + (ridx >> 2) * 8 + kg * 4 + (ridx & 3);
 }
 
-// One LDS tile of conserved keys against the wave's two row fragments.  The last tile of a (layer,
-// head) is padded with copies of the last conserved key: a copy ties with the original and the tie
-// rules (strict improvement, lowest register, lower slot between the lane groups) always prefer the
-// original, so no slot needs masking and there is a single code path.
+// The two lane groups of a wave saw disjoint slots of the same row: the better one, ties -> lower slot.
+__device__ __forceinline__ int row_best_merge(const RowBest& rb, int kg) {
+  const int mine = row_best_slot(rb, kg);
+  const float ov = __shfl_xor(rb.best, 32, kWave);
+  const int oi = __shfl_xor(mine, 32, kWave);
+  const bool take = ov > rb.best || (ov == rb.best && oi < mine);
+  return take ? oi : mine;
+}
+
+// One block of 32 conserved slots against the wave's two row fragments: fragment and 1/|k_j| from LDS, both
+// products (the two accumulator chains alternate), then scaling, maxima and the copy of an improved block.
+// With two waves per SIMD one wave's vector phase runs beside the other's matrix phase.  (Variants that
+// interleave the vector work of the previous block with the matrix instructions inside one wave, by hand or
+// through the scheduler, measured the same or slower on every workload: under random operands the chip is
+// limited by power, its clock drops to about 1.5 GHz in this kernel, and what counts is the number of
+// instructions and LDS bytes per block, not their order.)
+// The last tile of a (layer, head) is padded with copies of the last conserved key: a copy ties with the
+// original and the tie rules (strict improvement, lowest register, lower slot between the lane groups)
+// always prefer the original, so no slot needs masking and there is a single code path.
 template <typename T, int D>
-__device__ __forceinline__ void sim_tile(const char* ctile, const float* cinv, int s0, int n, int kg,
-                                         const Frag<T, D> (&lf)[2], RowBest (&rb)[2]) {
-  using TL = Tile<T, D>;
+__device__ __forceinline__ void sim_block_products(const char* block, const unsigned (&coff)[Tile<T, D>::kFragChunks],
+                                                   const Frag<T, D> (&lf)[2], f32x16_t (&acc)[2]) {
+  Frag<T, D> cf;
 #pragma unroll
-  for (int cb = 0; cb < kSimSlotTile / 32; ++cb) {
-    Frag<T, D> cf;
-    frag_load(cf, ctile + (cb * 32 + n) * TL::kStride, kg);
-    float iv[16];
-#pragma unroll
-    for (int r4 = 0; r4 < 4; ++r4) {
-      const float4 v = *reinterpret_cast<const float4*>(cinv + cb * 32 + r4 * 8 + kg * 4);
-      iv[r4 * 4 + 0] = v.x;
-      iv[r4 * 4 + 1] = v.y;
-      iv[r4 * 4 + 2] = v.z;
-      iv[r4 * 4 + 3] = v.w;
-    }
-    f32x16_t acc0 = acc_zero(), acc1 = acc_zero();
-    mma<T, D>(acc0, cf, lf[0]);
-    mma<T, D>(acc1, cf, lf[1]);
-    argmax_block(acc0, iv, s0 + cb * 32, rb[0]);
-    argmax_block(acc1, iv, s0 + cb * 32, rb[1]);
-  }
+  for (int c = 0; c < Tile<T, D>::kFragChunks; ++c) cf.c[c] = *reinterpret_cast<const uint4*>(block + coff[c]);
+  acc[0] = acc_zero();
+  acc[1] = acc_zero();
+  mma<T, D>(acc[0], cf, lf[0]);
+  mma<T, D>(acc[1], cf, lf[1]);
+}
+
+template <typename T, int D>
+__device__ __forceinline__ void sim_block_simple(const char* block, const unsigned (&coff)[Tile<T, D>::kFragChunks],
+                                                 const Frag<T, D> (&lf)[2], const float* iv_lds, int slot0, RowBest (&rb)[2]) {
+  float iv[16];
+  load_inv(iv, iv_lds);
+  f32x16_t acc[2];
+  sim_block_products<T, D>(block, coff, lf, acc);
+  const float bm0 = scale_max(acc[0], iv), bm1 = scale_max(acc[1], iv);
+  keep_if_improved(acc[0], bm0, slot0, rb[0]);
+  keep_if_improved(acc[1], bm1, slot0, rb[1]);
+}
+
+// Tiled kernel: grid over (row block of 256, kv head, layer); 4 waves x 64 less-important rows.  The conserved
+// keys stream through a ring of four LDS tiles of 64 slots, filled by asynchronous copies that go from global
+// memory straight into LDS (no registers, no LDS store instructions): while tile t is multiplied, tile t+1 has
+// landed, tile t+2 is landing and the copies of tile t+3 have just been issued, which gives every copy two tile
+// times to arrive; one wait and one barrier per tile.
+//
+// LDS layout of a tile: 64 rows, unpadded, 16-byte chunk c of row r at position c ^ swz(r) of the row.  A copy
+// instruction writes lane i's 16 bytes at (instruction base) + 16 i, so the rows cannot be padded; which global
+// chunk a lane fetches is free, and the xor spreads the 16 rows a fragment load touches in one pass over all
+// banks (rows of 256 bytes start at the same bank: swz(r) = r mod 16; two rows of 128 bytes share a bank
+// line: swz(r) = (r / 2) mod 8).
+// The 1/|k_j| of a tile are copied the same way (4 bytes per lane); every wave keeps its own copy, so all waves
+// issue the same number of copies per tile and wait for the same count.
+constexpr int kSimRing = 4;
+constexpr int kSimInvRing = 8;
+
+template <typename T, int D>
+constexpr int sim_tiled_lds_bytes() {
+  return kSimRing * kSimSlotTile * Tile<T, D>::kRowBytes + kSimInvRing * kSimWaves * kSimSlotTile * (int)sizeof(float);
+}
+
+template <typename T, int D>
+__device__ __forceinline__ int swizzle_of_row(int r) {
+  return Tile<T, D>::kRowBytes >= 256 ? (r & 15) : ((r >> 1) & 7);
 }
 
 template <typename T, int D>
 __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 ? 2 : 1)) similarity_argmax_kernel(MergeArgs a) {
   using TL = Tile<T, D>;
   constexpr int CPR = TL::kChunksPerRow;
-  constexpr int NTHR = kSimWaves * 64;
-  constexpr int PF = kSimSlotTile * CPR / NTHR;  // 16-byte pieces of a tile per thread
-  constexpr int ROWS_PER_PIECE_STEP = NTHR / CPR;
-  static_assert(kSimSlotTile * CPR % NTHR == 0 && NTHR % CPR == 0, "tile pieces must divide evenly over the threads");
-  __shared__ __align__(16) char ctile[2][kSimSlotTile * TL::kStride];
-  __shared__ __align__(16) float cinv[2][kSimSlotTile];
+  constexpr int NC = TL::kFragChunks;
+  constexpr int RPI = 64 / CPR;                        // rows one copy instruction fills
+  constexpr int PF = kSimSlotTile / RPI / kSimWaves;   // key copy instructions per wave and tile
+  constexpr int NB = kSimSlotTile / 32;                // blocks per tile
+  constexpr int KPT = PF + 1;                          // copies per wave and tile (keys and 1/|k|)
+  constexpr int kTileBytes = kSimSlotTile * TL::kRowBytes;
+  static_assert(kSimSlotTile % (RPI * kSimWaves) == 0, "the copy instructions must tile the rows of a tile evenly");
+  extern __shared__ __align__(16) char smem[];
+  char* ctile = smem;                                                       // [kSimRing][64 rows]
+  float* cinv = reinterpret_cast<float*>(smem + kSimRing * kTileBytes);     // [kSimInvRing][waves][64]
 
   // Workgroups are dealt round-robin to the 8 XCDs in launch order.  The launch index is remapped so
   // that all row blocks of one (layer, head) run on the same XCD (they stream the same conserved keys
@@ -160,11 +226,12 @@ __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 
   const int row_base = (seq % nrb) * kSimRows;
   if (row_base >= n_less) return;
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, kg = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, kg = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const long long off_l = a.off[l];
   const size_t cbase = (size_t)off_l * a.Hkv + (size_t)g * S;
-  const int32_t* cidx = a.sel_idx + cbase;
   const float* sinv = a.sel_inv_norm + cbase;
+  const char* pk = a.packed_k + cbase * TL::kRowBytes;  // this pair's conserved keys, contiguous
   const size_t lbase = less_base_of(l, g, a.T, a.Hkv, off_l, S);
   const int32_t* less = a.less_idx + lbase;
   const char* kbase = a.k;  // positions are stored as row ids over all layers and heads
@@ -176,66 +243,63 @@ __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 
 #pragma unroll
   for (int s = 0; s < 2; ++s) lrow[s] = less[min(r0 + s * 32 + n, n_less - 1)];
   RowBest rb[2];
-#pragma unroll
-  for (int s = 0; s < 2; ++s) {
-    rb[s].best = -INFINITY;
-    rb[s].slot0 = 0;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) rb[s].u[r] = -INFINITY;
-  }
-
-  // this thread's pieces of a tile: piece i is 16 bytes at row prow0 + i * ROWS_PER_PIECE_STEP, column pcc
-  const int prow0 = tid / CPR, pcc = tid - prow0 * CPR;
-  int pidx[PF];
-  uint4 pre[PF];
-#pragma unroll
-  for (int i = 0; i < PF; ++i) pre[i] = make_uint4(0, 0, 0, 0);
-  float piv = 0.f;
-  const int ntiles = (S + kSimSlotTile - 1) / kSimSlotTile;
-
-#define MEDA_SIM_LOAD_IDX(t)                                                      \
-  _Pragma("unroll") for (int i = 0; i < PF; ++i) {                                \
-    const int slot = (t) * kSimSlotTile + prow0 + i * ROWS_PER_PIECE_STEP;        \
-    pidx[i] = cidx[min(slot, S - 1)];                                             \
-  }
-#define MEDA_SIM_ISSUE(t)                                                                                \
-  _Pragma("unroll") for (int i = 0; i < PF; ++i) {                                                       \
-    pre[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)pidx[i] * TL::kRowBytes + pcc * 16);        \
-  }                                                                                                      \
-  if (tid < kSimSlotTile) piv = sinv[min((t) * kSimSlotTile + tid, S - 1)];
-#define MEDA_SIM_COMMIT(buf)                                                                             \
-  _Pragma("unroll") for (int i = 0; i < PF; ++i)                                                         \
-    *reinterpret_cast<uint4*>(ctile[buf] + (prow0 + i * ROWS_PER_PIECE_STEP) * TL::kStride + pcc * 16) = pre[i]; \
-  if (tid < kSimSlotTile) cinv[buf][tid] = piv;
-
-  MEDA_SIM_LOAD_IDX(0)
+  row_best_init(rb[0]);
+  row_best_init(rb[1]);
   Frag<T, D> lf[2];
 #pragma unroll
   for (int s = 0; s < 2; ++s) frag_load(lf[s], kbase + (size_t)lrow[s] * TL::kRowBytes, kg);
-  MEDA_SIM_ISSUE(0)
-  if (ntiles > 1) { MEDA_SIM_LOAD_IDX(1) }
-  MEDA_SIM_COMMIT(0)
-  for (int t = 0; t < ntiles; ++t) {
-    __syncthreads();  // tile t is in LDS; the other buffer is no longer read
-    if (t + 1 < ntiles) {
-      MEDA_SIM_ISSUE(t + 1)
-      if (t + 2 < ntiles) { MEDA_SIM_LOAD_IDX(t + 2) }
-    }
-    sim_tile<T, D>(ctile[t & 1], cinv[t & 1], t * kSimSlotTile, n, kg, lf, rb);
-    if (t + 1 < ntiles) { MEDA_SIM_COMMIT((t + 1) & 1) }
-  }
-#undef MEDA_SIM_LOAD_IDX
-#undef MEDA_SIM_ISSUE
-#undef MEDA_SIM_COMMIT
 
-  // the two lane groups saw disjoint slots of the same row: keep the better, ties -> lower slot
+  // Copy instruction j of this wave fills the rows (wave * PF + j) * RPI .. + RPI-1 of a tile: this lane brings
+  // one 16-byte chunk of row crow_r + j * RPI.  Slots past the end of the set repeat the last conserved key (see
+  // sim_block_simple).  Tiles past the last one repeat it too (they are never read; issuing them keeps the number
+  // of copies in flight the same in every iteration).
+  const int ntiles = (S + kSimSlotTile - 1) / kSimSlotTile;
+  const int crow_r = wave * PF * RPI + lane / CPR;
+  const unsigned lds_ring = (unsigned)(size_t)ctile, lds_inv = (unsigned)(size_t)cinv;
+  auto issue_tile = [&](int t, int ring_slot) {  // tile t of the stream into slot ring_slot of the rings
+    const int tc = min(t, ntiles - 1);
+#pragma unroll
+    for (int j = 0; j < PF; ++j) {
+      const int r = crow_r + j * RPI;   // row of the tile; its swizzle does not depend on the tile
+      const int slot = min(tc * kSimSlotTile + r, S - 1);
+      const unsigned goff = (unsigned)(slot * TL::kRowBytes + (((lane % CPR) ^ swizzle_of_row<T, D>(r)) * 16));
+      async_copy16_to_lds(pk, goff, lds_ring + (unsigned)((ring_slot % kSimRing) * kTileBytes + (wave * PF + j) * 1024));
+    }
+    const unsigned goff4 = (unsigned)(min(tc * kSimSlotTile + lane, S - 1) * 4);
+    const unsigned loff4 = (unsigned)((((ring_slot % kSimInvRing) * kSimWaves + wave) * kSimSlotTile) * 4);
+    async_copy4_to_lds(sinv, goff4, lds_inv + loff4);
+  };
+  issue_tile(0, 0);
+  issue_tile(1, 1);
+  issue_tile(2, 2);
+
+  // chunk c of this lane's fragment (chunk kg * NC + c of row n of a block) sits at (n * row bytes) +
+  // 16 * ((kg * NC + c) ^ swz(n)) inside a block of 32 rows
+  unsigned coff[NC];
+#pragma unroll
+  for (int c = 0; c < NC; ++c) coff[c] = (unsigned)(n * TL::kRowBytes + (((kg * NC + c) ^ swizzle_of_row<T, D>(n)) * 16));
+  // block cb of the tile in ring slot rs: its rows and where its 1/|k_j| start in this wave's copy
+  auto block_rows = [&](int rs, int cb) { return ctile + (rs % kSimRing) * kTileBytes + cb * 32 * TL::kRowBytes; };
+  auto inv_index = [&](int rs, int cb) { return ((rs % kSimInvRing) * kSimWaves + wave) * kSimSlotTile + cb * 32; };
+
+  async_copy_wait<KPT>();  // tiles 0 and 1 have landed (this wave's part)
+  __syncthreads();         // every wave's part has
+  issue_tile(3, 3);
+  for (int t = 0; t < ntiles; ++t) {
+    if (t > 0) {
+      async_copy_wait<KPT>();    // this wave's part of tile t+1 has landed; tile t+2 may still be in flight
+      __syncthreads();           // every wave's part has; and nobody reads tile t-1 any more
+      issue_tile(t + 3, t + 3);  // into the buffer of tile t-1
+    }
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb)
+      sim_block_simple<T, D>(block_rows(t, cb), coff, lf, cinv + inv_index(t, cb) + kg * 4, (t * NB + cb) * 32, rb);
+  }
+  async_copy_wait<0>();  // nothing of this wave is still on its way into LDS when it ends
+
 #pragma unroll
   for (int s = 0; s < 2; ++s) {
-    const int mine = row_best_slot(rb[s], kg);
-    const float ov = __shfl_xor(rb[s].best, 32, kWave);
-    const int oi = __shfl_xor(mine, 32, kWave);
-    const bool take = ov > rb[s].best || (ov == rb[s].best && oi < mine);
-    const int bi = take ? oi : mine;
+    const int bi = row_best_merge(rb[s], kg);
     const int ri = r0 + s * 32 + n;
     if (kg == 0 && ri < n_less) {
       a.less_slot[lbase + ri] = bi;
@@ -246,8 +310,7 @@ __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 
 
 // Variant for layers whose conserved set fits into LDS: one workgroup keeps ALL conserved keys of its
 // (layer, head) resident and every wave streams chunks of 64 less-important rows through registers.
-// After the prologue there is no barrier: the waves run independently, each MFMA phase of one wave
-// overlaps the argmax phase and the row loads of the others, and the keys are read from HBM once.
+// After the prologue there is no barrier: the waves run independently and the keys are read from HBM once.
 // grid (kResSplit * L * Hkv): part p of a pair takes the chunks p*8 + wave, then steps of 8*kResSplit.
 // Layers above the capacity are left to the tiled kernel above (and skipped there when they fit).
 template <typename T, int D>
@@ -270,8 +333,8 @@ __global__ void __launch_bounds__(kResThreads, 2) similarity_resident_kernel(Mer
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const long long off_l = a.off[l];
   const size_t cbase = (size_t)off_l * a.Hkv + (size_t)g * S;
-  const int32_t* cidx = a.sel_idx + cbase;
   const float* sinv = a.sel_inv_norm + cbase;
+  const char* pk = a.packed_k + cbase * TL::kRowBytes;  // this pair's conserved keys, contiguous
   const size_t lbase = less_base_of(l, g, a.T, a.Hkv, off_l, S);
   const int32_t* less = a.less_idx + lbase;
   const char* kbase = a.k;  // positions are stored as row ids over all layers and heads
@@ -290,25 +353,19 @@ __global__ void __launch_bounds__(kResThreads, 2) similarity_resident_kernel(Mer
 #pragma unroll
   for (int s = 0; s < 2; ++s) frag_load(lf[s], kbase + (size_t)lrow[s] * TL::kRowBytes, kg);
 
-  // Prologue: gather the conserved keys into LDS.  The set is padded to a multiple of 32 slots with
-  // copies of the last key (a copy can never win a tie against the original, see sim_tile).
+  // Prologue: the conserved keys into LDS.  The set is padded to a multiple of 32 slots with
+  // copies of the last key (a copy can never win a tie against the original, see sim_block_simple).
   const int S_pad = (S + 31) & ~31;
   char* ckeys = smem;
   float* cinv = reinterpret_cast<float*>(smem + (size_t)S_pad * TL::kStride);
   constexpr int kBatch = 6;  // pieces per thread whose loads are in flight together
   const int n_pieces = S_pad * CPR;
   for (int p0 = tid; p0 < n_pieces; p0 += kBatch * kResThreads) {
-    int ridx[kBatch];
     uint4 v[kBatch];
 #pragma unroll
     for (int i = 0; i < kBatch; ++i) {
       const int p = min(p0 + i * kResThreads, n_pieces - 1);
-      ridx[i] = cidx[min(p / CPR, S - 1)];
-    }
-#pragma unroll
-    for (int i = 0; i < kBatch; ++i) {
-      const int p = min(p0 + i * kResThreads, n_pieces - 1);
-      v[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)ridx[i] * TL::kRowBytes + (p % CPR) * 16);
+      v[i] = *reinterpret_cast<const uint4*>(pk + (unsigned)(min(p / CPR, S - 1) * TL::kRowBytes + (p % CPR) * 16));
     }
 #pragma unroll
     for (int i = 0; i < kBatch; ++i) {
@@ -319,6 +376,12 @@ __global__ void __launch_bounds__(kResThreads, 2) similarity_resident_kernel(Mer
   for (int sl = tid; sl < S_pad; sl += kResThreads) cinv[sl] = sinv[min(sl, S - 1)];
   __syncthreads();
 
+  const int nblocks = S_pad / 32;
+  unsigned coff[TL::kFragChunks];   // chunk c of this lane's fragment inside a block of 32 padded rows
+#pragma unroll
+  for (int c = 0; c < TL::kFragChunks; ++c) coff[c] = (unsigned)(n * TL::kStride + kg * TL::kHalfBytes + c * 16);
+  auto block_base = [&](int b) { return ckeys + b * 32 * TL::kStride; };
+  auto block_inv = [&](int b) { return cinv + b * 32 + kg * 4; };
   while (c < n_chunks) {
     // the rows of the wave's next chunk and the row ids of the one after it are in flight while
     // this chunk is multiplied (past the last chunk they repeat the last row and are dropped)
@@ -329,39 +392,12 @@ __global__ void __launch_bounds__(kResThreads, 2) similarity_resident_kernel(Mer
     int nnrow[2];
     chunk_rows(c + 2 * kChunkStep, nnrow);
     RowBest rb[2];
+    row_best_init(rb[0]);
+    row_best_init(rb[1]);
+    for (int b = 0; b < nblocks; ++b) sim_block_simple<T, D>(block_base(b), coff, lf, block_inv(b), b * 32, rb);
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-      rb[s].best = -INFINITY;
-      rb[s].slot0 = 0;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) rb[s].u[r] = -INFINITY;
-    }
-    for (int s0 = 0; s0 < S_pad; s0 += 32) {
-      Frag<T, D> cf;
-      frag_load(cf, ckeys + (s0 + n) * TL::kStride, kg);
-      float iv[16];
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const float4 v = *reinterpret_cast<const float4*>(cinv + s0 + r4 * 8 + kg * 4);
-        iv[r4 * 4 + 0] = v.x;
-        iv[r4 * 4 + 1] = v.y;
-        iv[r4 * 4 + 2] = v.z;
-        iv[r4 * 4 + 3] = v.w;
-      }
-      f32x16_t acc0 = acc_zero(), acc1 = acc_zero();
-      mma<T, D>(acc0, cf, lf[0]);
-      mma<T, D>(acc1, cf, lf[1]);
-      argmax_block(acc0, iv, s0, rb[0]);
-      argmax_block(acc1, iv, s0, rb[1]);
-    }
-    // the two lane groups saw disjoint slots of the same row: keep the better, ties -> lower slot
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      const int mine = row_best_slot(rb[s], kg);
-      const float ov = __shfl_xor(rb[s].best, 32, kWave);
-      const int oi = __shfl_xor(mine, 32, kWave);
-      const bool take = ov > rb[s].best || (ov == rb[s].best && oi < mine);
-      const int bi = take ? oi : mine;
+      const int bi = row_best_merge(rb[s], kg);
       const int ri = r0 + s * 32 + n;
       if (kg == 0 && ri < n_less) {
         a.less_slot[lbase + ri] = bi;
@@ -374,6 +410,37 @@ __global__ void __launch_bounds__(kResThreads, 2) similarity_resident_kernel(Mer
       lrow[s] = nrow[s];
       nrow[s] = nnrow[s];
       lf[s] = lfn[s];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------ conserved keys, packed
+// Output row w of the ragged cache is the conserved key sel_idx[w]; the rows of one (layer, head) are
+// consecutive in w.  Copying them once into that order makes every tile of conserved keys the similarity
+// kernels stream a contiguous block (which a lane-addressed asynchronous copy into LDS needs).
+// 256 rows per workgroup.
+constexpr int kPackRows = 256;
+template <typename T, int D>
+__global__ void __launch_bounds__(256) pack_conserved_kernel(MergeArgs a) {
+  using TL = Tile<T, D>;
+  constexpr int LPR = TL::kChunksPerRow;   // lanes per row
+  constexpr int RPP = 256 / LPR;           // rows per pass
+  constexpr int U = 4;                     // passes whose loads are in flight together
+  static_assert(kPackRows % (RPP * U) == 0, "passes must tile the workgroup's rows");
+  const int tid = threadIdx.x;
+  const long long w0 = (long long)blockIdx.x * kPackRows, total = a.total_slots;
+  const int sub = tid / LPR, cc = tid - sub * LPR;
+  for (int r0 = 0; r0 < kPackRows; r0 += RPP * U) {
+    int idx[U];
+    uint4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) idx[u] = a.sel_idx[min(w0 + r0 + u * RPP + sub, total - 1)];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = load16_stream(a.k + (size_t)idx[u] * TL::kRowBytes + cc * 16);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const long long w = w0 + r0 + u * RPP + sub;
+      if (w < total) *reinterpret_cast<uint4*>(a.packed_k + (size_t)w * TL::kRowBytes + cc * 16) = v[u];
     }
   }
 }
@@ -820,6 +887,7 @@ static MergeArgs make_args(const Plan& p, const Buffers& b) {
   a.off = reinterpret_cast<const int64_t*>(b.ws + p.off_layer_off);
   a.sel_idx = reinterpret_cast<const int32_t*>(b.ws + p.off_sel_idx);
   a.sel_inv_norm = reinterpret_cast<const float*>(b.ws + p.off_sel_inv);
+  a.packed_k = b.ws + p.off_packed_k;
   a.less_idx = reinterpret_cast<const int32_t*>(b.ws + p.off_less_idx);
   a.less_slot = reinterpret_cast<int32_t*>(b.ws + p.off_less_slot);
   a.sort_key[0] = reinterpret_cast<int32_t*>(b.ws + p.off_sort_a);
@@ -837,18 +905,41 @@ static MergeArgs make_args(const Plan& p, const Buffers& b) {
   return a;
 }
 
+// Raises a kernel's dynamic LDS limit once per device (the attribute is a property of the loaded function).
+template <typename K>
+static hipError_t allow_dynamic_lds(K kernel, int bytes) {
+  static bool done[64] = {false};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev >= 0 && dev < 64 && done[dev]) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && dev >= 0 && dev < 64) done[dev] = true;
+  return e;
+}
+
 template <typename T, int D>
 static hipError_t launch_sim_t(const Plan& p, MergeArgs a, hipStream_t s) {
   const unsigned nrb = (p.T + kSimRows - 1) / kSimRows, pairs = (unsigned)(p.L * p.Hkv);
   // one resident-set workgroup occupies a whole CU: only worth it with at least one per CU
   a.use_resident = (resident_capacity<T, D>() > 0 && pairs >= 256u) ? 1 : 0;
-  dim3 grid(8u * nrb * ((pairs + 7u) / 8u));
-  hipLaunchKernelGGL((similarity_argmax_kernel<T, D>), grid, dim3(kSimWaves * 64), 0, s, a);
+  hipLaunchKernelGGL((pack_conserved_kernel<T, D>), dim3((unsigned)((a.total_slots + kPackRows - 1) / kPackRows)),
+                     dim3(256), 0, s, a);
   hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  dim3 grid(8u * nrb * ((pairs + 7u) / 8u));
+  constexpr int kTiledLds = sim_tiled_lds_bytes<T, D>();
+  auto tiled = similarity_argmax_kernel<T, D>;
+  if (kTiledLds > 64 * 1024) {
+    e = allow_dynamic_lds(tiled, kTiledLds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(tiled, grid, dim3(kSimWaves * 64), kTiledLds, s, a);
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (!a.use_resident) return hipSuccess;
   auto res = similarity_resident_kernel<T, D>;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(res), hipFuncAttributeMaxDynamicSharedMemorySize, kResLdsBytes);
+  e = allow_dynamic_lds(res, kResLdsBytes);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(res, dim3(pairs * kResSplit), dim3(kResThreads), kResLdsBytes, s, a);
   return hipGetLastError();

@@ -46,7 +46,7 @@ struct Plan {
   int accumulate;    // add to column scores / entropy partials instead of storing (every block but the first)
   // workspace regions (byte offsets)
   size_t off_stats_part, off_stats, off_inv_norm, off_col_scores, off_ent_part, off_alloc, off_layer_off,
-      off_sel_idx, off_sel_inv, off_less_idx, off_less_slot, off_sort_a, off_sort_b, off_sort_c, off_sort_d, off_seg_beg, off_seg_end, total_bytes;
+      off_sel_idx, off_sel_inv, off_packed_k, off_less_idx, off_less_slot, off_sort_a, off_sort_b, off_sort_c, off_sort_d, off_seg_beg, off_seg_end, total_bytes;
   size_t n_less_total;  // (L*T - B) * Hkv
 };
 
