@@ -215,15 +215,20 @@ def measured_peaks(pkg, torch, dev):
     ms_read = median_ms(lambda: pkg.meda_peak_stream_read(buf, sink))
     total = [0]
 
-    def mfma():
-        total[0] = pkg.meda_peak_mfma_bf16(1 << 16, sink)
-    ms_mfma = median_ms(mfma)
+    def mfma(random_operands):
+        def run():
+            total[0] = pkg.meda_peak_mfma_bf16(1 << 17, sink, random_operands)
+        return run
+    ms_mfma = median_ms(mfma(False))
+    ms_mfma_rnd = median_ms(mfma(True))
     del buf
     return {"hbm_read_GBps": (2 << 30) / (ms_read * 1e-3) / 1e9,
             "bf16_mfma_TFLOPs": total[0] * 32768.0 / (ms_mfma * 1e-3) / 1e12,
+            # the same instruction stream on operands whose bits toggle: the power-limited rate real data allows
+            "bf16_mfma_random_operands_TFLOPs": total[0] * 32768.0 / (ms_mfma_rnd * 1e-3) / 1e12,
             "published": {"hbm_GBps": HBM_PEAK_GBS, "bf16_mfma_TFLOPs": MFMA_PEAK_TFLOPS["bf16"]},
-            "how": "meda_peak_stream_read over 2 GiB; meda_peak_mfma_bf16, 65536 32x32x16 instructions per wave, "
-                   "2 waves per SIMD; median of 5 launches"}
+            "how": "meda_peak_stream_read over 2 GiB; meda_peak_mfma_bf16, 131072 32x32x16 instructions per wave, "
+                   "2 waves per SIMD, nearly constant and pseudo-random operands; median of 5 launches"}
 
 
 def _cpu_info():

@@ -237,10 +237,14 @@ meda_status meda_decode_attention_fp8(const meda_decode_params* params, const vo
  *                           >= 16) bf16 32x32x16 matrix instructions from registers, two waves per SIMD, four
  *                           independent accumulator chains per wave; *total_mfma (host pointer) receives the
  *                           number issued over the whole chip.  Rate = total_mfma * 32768 flop / time.
+ *                           random_operands = 0: operands nearly constant; 1: pseudo-random signs and mantissas
+ *                           (more bits toggle per step, the chip draws more power and holds a lower clock: the
+ *                           rate a kernel working on real data can hope for).
  * `sink` is a 4-byte aligned device word that is never actually written (it keeps the work alive).
  */
 meda_status meda_peak_stream_read(const void* src, size_t bytes, void* sink, void* hip_stream);
-meda_status meda_peak_mfma_bf16(int64_t mfma_per_wave, int64_t* total_mfma, void* sink, void* hip_stream);
+meda_status meda_peak_mfma_bf16(int64_t mfma_per_wave, int32_t random_operands, int64_t* total_mfma, void* sink,
+                                void* hip_stream);
 
 #ifdef __cplusplus
 }

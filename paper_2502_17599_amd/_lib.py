@@ -89,7 +89,7 @@ def load_library() -> ctypes.CDLL:
     lib.meda_peak_stream_read.restype = ctypes.c_int
     lib.meda_peak_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     lib.meda_peak_mfma_bf16.restype = ctypes.c_int
-    lib.meda_peak_mfma_bf16.argtypes = [ctypes.c_int64, ctypes.POINTER(ctypes.c_int64), vp, vp]
+    lib.meda_peak_mfma_bf16.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64), vp, vp]
     lib.meda_quantize_fp8.restype = ctypes.c_int
     lib.meda_quantize_fp8.argtypes = [vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, vp, vp, vp]
     lib.meda_dequantize_fp8.restype = ctypes.c_int
@@ -316,11 +316,11 @@ def meda_peak_stream_read(buf: torch.Tensor, sink: torch.Tensor, stream=None) ->
                                                 ctypes.c_void_p(stream.cuda_stream)))
 
 
-def meda_peak_mfma_bf16(mfma_per_wave: int, sink: torch.Tensor, stream=None) -> int:
+def meda_peak_mfma_bf16(mfma_per_wave: int, sink: torch.Tensor, random_operands: bool = False, stream=None) -> int:
     """Enqueue the matrix-instruction micro-kernel (measurement aid); returns the instructions issued chip-wide."""
     stream = stream if stream is not None else torch.cuda.current_stream(sink.device)
     total = ctypes.c_int64(0)
-    _check(load_library().meda_peak_mfma_bf16(int(mfma_per_wave), ctypes.byref(total), _ptr(sink),
+    _check(load_library().meda_peak_mfma_bf16(int(mfma_per_wave), 1 if random_operands else 0, ctypes.byref(total), _ptr(sink),
                                               ctypes.c_void_p(stream.cuda_stream)))
     return int(total.value)
 

@@ -121,6 +121,27 @@ meda_status make_plan(const meda_params* p, Plan* out) {
   return MEDA_OK;
 }
 
+// Kernels whose dynamic LDS limit has been raised, per device (a few dozen template instantiations at most).
+hipError_t allow_dynamic_lds(const void* kernel, int bytes) {
+  struct Entry { const void* fn; int bytes; unsigned long long devices; };
+  static std::mutex mu;
+  static std::vector<Entry> seen;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool tracked = dev >= 0 && dev < 64;
+  std::lock_guard<std::mutex> lk(mu);
+  Entry* entry = nullptr;
+  for (Entry& en : seen)
+    if (en.fn == kernel && en.bytes >= bytes) entry = &en;
+  if (entry && tracked && ((entry->devices >> dev) & 1ull)) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e != hipSuccess || !tracked) return e;
+  if (entry) entry->devices |= 1ull << dev;
+  else seen.push_back(Entry{kernel, bytes, 1ull << dev});
+  return hipSuccess;
+}
+
 // ------------------------------------------------------------------------------------- profiling
 struct CallEvents {
   hipEvent_t ev[MEDA_N_PHASES + 1];

@@ -905,19 +905,6 @@ static MergeArgs make_args(const Plan& p, const Buffers& b) {
   return a;
 }
 
-// Raises a kernel's dynamic LDS limit once per device (the attribute is a property of the loaded function).
-template <typename K>
-static hipError_t allow_dynamic_lds(K kernel, int bytes) {
-  static bool done[64] = {false};
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) return e;
-  if (dev >= 0 && dev < 64 && done[dev]) return hipSuccess;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-  if (e == hipSuccess && dev >= 0 && dev < 64) done[dev] = true;
-  return e;
-}
-
 template <typename T, int D>
 static hipError_t launch_sim_t(const Plan& p, MergeArgs a, hipStream_t s) {
   const unsigned nrb = (p.T + kSimRows - 1) / kSimRows, pairs = (unsigned)(p.L * p.Hkv);

@@ -34,22 +34,43 @@ __global__ void __launch_bounds__(kPeakThreads) peak_stream_read_kernel(const ui
   if (acc == 0x9e3779b9u) *sink = acc;
 }
 
-// Four independent accumulator chains per wave, operands made up from the lane id; one workgroup = one wave per
-// SIMD, two workgroups per CU.  Nothing is loaded; the sum of the accumulators is stored under a condition that
-// is false for these operands.
-__global__ void __launch_bounds__(kPeakThreads, 2) peak_mfma_bf16_kernel(long long rounds, float* sink) {
+// Four independent accumulator chains per wave, eight operand pairs per wave held in registers; one workgroup =
+// one wave per SIMD, two workgroups per CU.  Nothing is loaded; the sum of the accumulators is stored under a
+// condition that is false for these operands.  The operands are either nearly constant (bf16 values near 1,
+// the same in most lanes) or pseudo-random (sign, mantissa and the lowest exponent bit vary from lane to lane and
+// from step to step): the matrix unit's power draw, and with it the clock the chip can hold, depends on how many
+// operand bits toggle, so the two give different rates.
+__global__ void __launch_bounds__(kPeakThreads, 2) peak_mfma_bf16_kernel(long long rounds, int random_operands, float* sink) {
   const uint32_t seed = 0x3f803f80u + (threadIdx.x & 7u);  // pairs of bf16 values near 1
-  const uint4 a4 = make_uint4(seed, seed ^ 0x00010000u, seed, seed ^ 0x00000001u);
-  const uint4 b4 = make_uint4(seed ^ 0x00020002u, seed, seed ^ 0x00010001u, seed);
-  const bf16x8_t a = __builtin_bit_cast(bf16x8_t, a4), b = __builtin_bit_cast(bf16x8_t, b4);
+  uint4 a4[8], b4[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a4[i] = make_uint4(seed, seed ^ 0x00010000u, seed, seed ^ 0x00000001u);
+    b4[i] = make_uint4(seed ^ 0x00020002u, seed, seed ^ 0x00010001u, seed);
+  }
+  if (random_operands) {
+    uint32_t h = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+    auto word = [&]() {  // two bf16 values of magnitude 0.5 .. 2 with random sign and mantissa
+      h = h * 1664525u + 1013904223u;
+      const uint32_t v = h >> 8;
+      return ((v & 0x80ffu) | 0x3f00u) | ((((v >> 12) & 0x80ffu) | 0x3f00u) << 16);
+    };
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      a4[i] = make_uint4(word(), word(), word(), word());
+      b4[i] = make_uint4(word(), word(), word(), word());
+    }
+  }
   f32x16_t c0 = acc_zero(), c1 = acc_zero(), c2 = acc_zero(), c3 = acc_zero();
   for (long long r = 0; r < rounds; ++r) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
+      const bf16x8_t a = __builtin_bit_cast(bf16x8_t, a4[(2 * u) & 7]), b = __builtin_bit_cast(bf16x8_t, b4[(2 * u) & 7]);
+      const bf16x8_t a2 = __builtin_bit_cast(bf16x8_t, a4[(2 * u + 1) & 7]), b2 = __builtin_bit_cast(bf16x8_t, b4[(2 * u + 1) & 7]);
       c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
-      c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
-      c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
-      c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+      c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, b2, c1, 0, 0, 0);
+      c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b2, c2, 0, 0, 0);
+      c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, b, c3, 0, 0, 0);
     }
   }
   float s = 0.f;
@@ -77,7 +98,8 @@ meda_status meda_peak_stream_read(const void* src, size_t bytes, void* sink, voi
   return hipGetLastError() == hipSuccess ? MEDA_OK : MEDA_ERR_HIP;
 }
 
-meda_status meda_peak_mfma_bf16(int64_t mfma_per_wave, int64_t* total_mfma, void* sink, void* hip_stream) {
+meda_status meda_peak_mfma_bf16(int64_t mfma_per_wave, int32_t random_operands, int64_t* total_mfma, void* sink,
+                                void* hip_stream) {
   if (mfma_per_wave < 16 || mfma_per_wave > (1ll << 30) || !total_mfma || !sink || ((uintptr_t)sink & 3u))
     return MEDA_ERR_INVALID_ARG;
   int dev = 0, cus = 256;
@@ -86,7 +108,7 @@ meda_status meda_peak_mfma_bf16(int64_t mfma_per_wave, int64_t* total_mfma, void
   const long long rounds = mfma_per_wave / 16;  // 16 matrix instructions per round
   const unsigned blocks = (unsigned)cus * 2u;   // two waves per SIMD
   hipLaunchKernelGGL(meda::peak_mfma_bf16_kernel, dim3(blocks), dim3(meda::kPeakThreads), 0,
-                     static_cast<hipStream_t>(hip_stream), rounds, static_cast<float*>(sink));
+                     static_cast<hipStream_t>(hip_stream), rounds, random_operands ? 1 : 0, static_cast<float*>(sink));
   if (hipGetLastError() != hipSuccess) return MEDA_ERR_HIP;
   *total_mfma = (int64_t)rounds * 16 * (meda::kPeakThreads / 64) * blocks;
   return MEDA_OK;

@@ -66,6 +66,14 @@ struct Buffers {
   char* ws;
 };
 
+// Raises a kernel's dynamic LDS limit once per (kernel, device): the attribute is a property of the loaded
+// function, and a host call per launch would sit on the critical path of the small workloads.
+hipError_t allow_dynamic_lds(const void* kernel, int bytes);
+template <typename K>
+inline hipError_t allow_dynamic_lds(K kernel, int bytes) {
+  return allow_dynamic_lds(reinterpret_cast<const void*>(kernel), bytes);
+}
+
 // kernel launchers (one per phase); each returns the hipError_t of its launch
 hipError_t launch_score_stats(const Plan&, const Buffers&, hipStream_t);
 hipError_t launch_stats_combine(const Plan&, const Buffers&, hipStream_t);

@@ -445,8 +445,7 @@ static hipError_t launch_stats_w(const Plan& p, const ScoreArgs& a, hipStream_t 
   const size_t lds = (size_t)kScoreTile * Tile<T, D>::kStride + kScoreTile;
   auto kern = score_stats_kernel<T, D, NQ, NW>;
   if (lds > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = allow_dynamic_lds(kern, (int)lds);
     if (e != hipSuccess) return e;
   }
   dim3 grid(p.NCH, p.Hkv, p.L), block(NW * 64);
@@ -487,8 +486,7 @@ static hipError_t launch_accum_k(const Plan& p, const ScoreArgs& a, hipStream_t 
                      NW * 2 * sizeof(double);
   auto kern = score_accum_kernel<T, D, RB, KSTAGE, NW>;
   if (lds > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = allow_dynamic_lds(kern, (int)lds);
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(kern, dim3(p.NT, p.L), dim3(NW * 64), lds, s, a);
