@@ -49,7 +49,7 @@ typedef enum { MEDA_F32 = 0, MEDA_BF16 = 1 } meda_dtype;
 #define MEDA_FLAG_FULL_PROMPT 4    /* every prompt position scores the keys (Section 3.3 sums A_p over all
                                       prompt rows, Section 3.2 takes all text / vision queries): q_win
                                       is then [L][Hq][T][d]; `window` stays the lower bound of the recent
-                                      part and of the layer budgets; needs Hq / Hkv <= 8                */
+                                      part and of the layer budgets                                    */
 
 typedef struct {
   int32_t n_layers;     /* L, 1..256                                                               */
@@ -112,7 +112,8 @@ meda_status meda_compress(const meda_params* params, const void* q_win, const vo
 typedef enum {
   MEDA_REGION_COL_SCORES = 0, /* float [L][Hkv][T]: cumulative attention score A_s (Section 3.3)    */
   MEDA_REGION_INV_NORM = 1,   /* float [L][Hkv][T]: 1/|k| of every key                              */
-  MEDA_REGION_ROW_STATS = 2,  /* float [L][Hq][Wp][4], Wp = W rounded up to 32: log2-domain row max,
+  MEDA_REGION_ROW_STATS = 2,  /* float [L][Hq][Wp][4], Wp = W rounded up to 32 (with MEDA_FLAG_FULL_PROMPT and
+                                 T > 128: [L][Hq][T][4], one row per position): log2-domain row max,
                                  1/Z over all visible keys, then the row's cross-modal 1/Z as the factor
                                  for vision columns (text rows, else 0) and for text columns (vision
                                  rows, else 0)                                                        */

@@ -11,21 +11,34 @@ namespace meda {
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// Tiling of the two scoring passes for w query rows (the last w positions) of a sequence of t keys.
-static bool score_geometry(Plan* pl, int t, int w) {
+// Tiling of the two scoring passes for w query rows (the last w positions) of a sequence of t keys.  With
+// `single_chunk` a pass-A workgroup walks all keys its rows see (used when every prompt row scores: the row blocks
+// already give that launch tens of thousands of workgroups).
+static bool score_geometry(Plan* pl, int t, int w, bool single_chunk) {
   pl->Tb = t;
   pl->Wb = w;
   pl->RB = (w + 31) / 32;
   pl->Wp = pl->RB * 32;
-  const int combos = pl->G * pl->RB;
-  if (combos > 32) return false;
+  // Row blocks of one pass-A workgroup.  When every prompt row scores (single_chunk), pass A cuts the rows into its
+  // own, larger blocks: about 16 (head, 32-row block) pairs per workgroup, so a key tile staged in LDS serves 512
+  // rows without head grouping (the keys are re-read once per row block of pass A).
+  pl->RBa = pl->RB;
+  if (single_chunk) {
+    const int want = pl->G >= 16 ? 1 : 16 / pl->G;
+    const int have = (t + 31) / 32;
+    pl->RBa = want < have ? want : have;
+  }
+  pl->row_block_a = pl->RBa * 32;
+  pl->n_blocks_a = single_chunk ? (t + pl->row_block_a - 1) / pl->row_block_a : 1;
+  const int combos = pl->G * pl->RBa;
+  if (combos > 32 || pl->RB > 4) return false;
   pl->NQ = combos <= 4 ? 1 : (combos <= 16 ? 2 : 4);  // (head, row block) pairs a wave keeps in registers
   pl->NCG = (combos + pl->NQ - 1) / pl->NQ;
   pl->CS = (pl->NCG <= 4) ? 4 / pl->NCG : 1;
   const int tiles = (t + kScoreTile - 1) / kScoreTile;
   pl->NT = tiles;
   const int64_t units = (int64_t)pl->L * pl->Hkv;
-  int64_t nch = (4096 + units - 1) / units;
+  int64_t nch = single_chunk ? 1 : (4096 + units - 1) / units;
   if (nch < 1) nch = 1;
   if (nch > tiles) nch = tiles;
   const int tiles_per_chunk = (int)((tiles + nch - 1) / nch);
@@ -33,16 +46,6 @@ static bool score_geometry(Plan* pl, int t, int w) {
   pl->NCH = (t + pl->CH - 1) / pl->CH;
   pl->NPART = pl->NCH * pl->CS;
   return true;
-}
-
-Plan score_block_plan(const Plan& whole, int bi) {
-  Plan sub = whole;
-  const int t_eff = whole.Tk - bi * kScoreRowBlock;             // keys the block's last row sees
-  const int w_b = t_eff < kScoreRowBlock ? t_eff : kScoreRowBlock;
-  score_geometry(&sub, t_eff, w_b);                             // cannot fail: not more rows than block 0
-  sub.q_row0 = t_eff - w_b;
-  sub.accumulate = bi > 0;
-  return sub;
 }
 
 meda_status make_plan(const meda_params* p, Plan* out) {
@@ -84,21 +87,17 @@ meda_status make_plan(const meda_params* p, Plan* out) {
   pl.q_row0 = 0;
   pl.NTk = (pl.T + kScoreTile - 1) / kScoreTile;
   pl.accumulate = 0;
-  // scoring geometry of the largest block (the only one without the flag); the workspace holds the
-  // row statistics of one block at a time, sized for the block that needs most
+  // Scoring geometry.  With every prompt row scoring, one launch of each scoring kernel covers all row blocks
+  // (the kernels derive a block's key count and rows themselves) and the row statistics hold all R = T rows.
   const int w_score = full_prompt ? (pl.T < kScoreRowBlock ? pl.T : kScoreRowBlock) : pl.W;
-  if (!score_geometry(&pl, pl.T, w_score)) return MEDA_ERR_UNSUPPORTED;
-  int max_wp = pl.Wp, max_npart = pl.NPART;
-  for (int bi = 1; bi < pl.n_blocks; ++bi) {
-    const Plan sub = score_block_plan(pl, bi);
-    if (sub.Wp * sub.NPART > max_wp * max_npart) { max_wp = sub.Wp; max_npart = sub.NPART; }
-  }
+  if (!score_geometry(&pl, pl.T, w_score, pl.n_blocks > 1)) return MEDA_ERR_UNSUPPORTED;
+  const size_t stats_rows = pl.n_blocks > 1 ? (size_t)pl.R : (size_t)pl.Wp;
 
   pl.n_less_total = (size_t)((int64_t)pl.L * pl.T - pl.B) * pl.Hkv;
   size_t o = 0;
   auto take = [&](size_t bytes) { const size_t at = o; o = align_up(o + bytes, 256); return at; };
-  pl.off_stats_part = take((size_t)pl.L * pl.Hq * max_wp * max_npart * 16);
-  pl.off_stats = take((size_t)pl.L * pl.Hq * pl.Wp * 16);
+  pl.off_stats_part = take((size_t)pl.L * pl.Hq * stats_rows * pl.NPART * 16);
+  pl.off_stats = take((size_t)pl.L * pl.Hq * stats_rows * 16);
   pl.off_inv_norm = take((size_t)pl.L * pl.Hkv * pl.T * 4);
   pl.off_col_scores = take((size_t)pl.L * pl.Hkv * pl.T * 4);
   pl.off_ent_part = take((size_t)pl.L * pl.NTk * 2 * 8);
@@ -189,7 +188,10 @@ meda_status meda_workspace_region(const meda_params* params, int region, size_t*
   switch (region) {
     case MEDA_REGION_COL_SCORES: *offset = pl.off_col_scores; *bytes = (size_t)pl.L * pl.Hkv * pl.T * 4; break;
     case MEDA_REGION_INV_NORM: *offset = pl.off_inv_norm; *bytes = (size_t)pl.L * pl.Hkv * pl.T * 4; break;
-    case MEDA_REGION_ROW_STATS: *offset = pl.off_stats; *bytes = (size_t)pl.L * pl.Hq * pl.Wp * 16; break;
+    case MEDA_REGION_ROW_STATS:
+      *offset = pl.off_stats;
+      *bytes = (size_t)pl.L * pl.Hq * (pl.n_blocks > 1 ? (size_t)pl.R : (size_t)pl.Wp) * 16;
+      break;
     case MEDA_REGION_ALLOC: *offset = pl.off_alloc; *bytes = (size_t)pl.L * 16; break;
     case MEDA_REGION_LESS_IDX: *offset = pl.off_less_idx; *bytes = pl.n_less_total * 4; break;
     case MEDA_REGION_LESS_SLOT: *offset = pl.off_less_slot; *bytes = pl.n_less_total * 4; break;
@@ -227,18 +229,7 @@ meda_status meda_compress(const meda_params* params, const void* q_win, const vo
   if (prof && ce.only <= 0) err = hipEventRecord(ce.ev[0], s);
   for (int i = 0; i < MEDA_N_PHASES && err == hipSuccess; ++i) {
     const bool skip = no_merge && (i == 5 || i == 6);
-    if (i == 0 && pl.n_blocks > 1) {
-      // every prompt row scores: the three scoring kernels run once per row block, last block first (the
-      // first launch stores column scores and entropy partials, the others add); all of it is timed as phase 0
-      for (int bi = 0; bi < pl.n_blocks && err == hipSuccess; ++bi) {
-        const Plan sub = score_block_plan(pl, bi);
-        for (int j = 0; j < 3 && err == hipSuccess; ++j) err = phases[j](sub, b, s);
-      }
-    } else if (i <= 2 && pl.n_blocks > 1) {
-      // done above
-    } else if (!skip) {
-      err = phases[i](pl, b, s);
-    }
+    if (!skip) err = phases[i](pl, b, s);
     const bool rec = prof && (ce.only < 0 || i == ce.only || i + 1 == ce.only);
     if (rec && err == hipSuccess) err = hipEventRecord(ce.ev[i + 1], s);
   }

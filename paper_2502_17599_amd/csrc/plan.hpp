@@ -16,7 +16,7 @@ constexpr int kSimWaves = 4;
 constexpr int kSimRows = kSimRowsPerWave * kSimWaves;  // less-important rows per workgroup
 constexpr int kSimSlotTile = 64;                       // conserved slots staged in LDS per step
 constexpr int kMaxLayers = 256;
-constexpr int kScoreRowBlock = 128;  // query rows per scoring launch when every prompt row scores
+constexpr int kScoreRowBlock = 128;  // query rows per row block of pass B when every prompt row scores
 
 struct Plan {
   // problem.  A batch of N sequences is laid out as N * Lseq "layers": every kernel but the budget
@@ -29,15 +29,17 @@ struct Plan {
   float scale_log2;  // softmax scale times log2(e): logits are kept in the base-2 domain
   int elt;           // bytes per element
   // scoring
-  int RB, Wp;        // 32-row blocks of the window, padded window
+  int RB, Wp;        // 32-row blocks of the window (of a 128-row block when every prompt row scores), padded window
+  int RBa;           // 32-row blocks of one pass-A workgroup (RB, or more when every prompt row scores)
+  int row_block_a, n_blocks_a;  // rows per row block of pass A and their number (every prompt row scores)
   int NQ, NCG, CS;   // pass A: (head, row block) pairs per wave, wave groups, column split
   int CH, NCH, NPART;  // pass A: columns per chunk, chunks, partial statistics per row
   int NT;            // pass B: column tiles
   // Scoring rows.  Normally the W window rows (R == W).  With MEDA_FLAG_FULL_PROMPT every prompt position
-  // scores (R == T) and the scoring passes run once per block of at most kScoreRowBlock rows, last block
-  // first: a block of rows [q_row0, q_row0 + Wb) sees only the keys below Tb = q_row0 + Wb, so it is the window
-  // computation of a sequence cut after its last row (score_block_plan sets the fields below for one block).
-  int Tb, Wb;        // keys and query rows of this scoring launch (T and W without the flag)
+  // scores (R == T): the rows are cut into n_blocks blocks of at most kScoreRowBlock rows counted from the end; a
+  // block of rows [Tb - Wb, Tb) sees only the keys below Tb, so it is the window computation of a sequence cut
+  // after its last row.  One launch of each scoring kernel covers all blocks (the kernels derive Tb, Wb themselves).
+  int Tb, Wb;        // keys and query rows of the scoring launch (T and W; with the flag: T and the block size)
   int R;             // scoring rows in total; rows per (layer, head) in the query buffer
   int n_blocks;      // row blocks
   int Tk;            // key rows per (layer, kv head) in memory (T of the whole sequence)
@@ -51,8 +53,6 @@ struct Plan {
 };
 
 meda_status make_plan(const meda_params* p, Plan* plan);
-// The plan of scoring block `bi` (0 = the last rows of the prompt) of a plan made by make_plan.
-Plan score_block_plan(const Plan& whole, int bi);
 
 struct Buffers {
   const void *q, *k, *v;

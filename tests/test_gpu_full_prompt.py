@@ -53,13 +53,19 @@ def test_full_prompt_group_of_eight_and_short_sequence():
                   total_budget=2 * 40, seed=6, score_rows=96))
 
 
-def test_full_prompt_rejects_large_groups():
-    import torch
-    import paper_2502_17599_amd as pkg
-    p = pkg.make_params(2, 16, 1, 128, 512, 32, 2 * 100, torch.bfloat16, flags=pkg.FLAG_FULL_PROMPT)
-    assert pkg.meda_workspace_bytes(p) == 0          # 16 query heads per kv head with 128-row blocks
-    p = pkg.make_params(2, 8, 1, 128, 512, 32, 2 * 100, torch.bfloat16, flags=pkg.FLAG_FULL_PROMPT)
-    assert pkg.meda_workspace_bytes(p) > 0
+def test_full_prompt_sixteen_query_heads_per_kv_head():
+    # pass A then holds one 32-row block of each of the 16 heads per workgroup; T = 300 leaves ragged row blocks in both
+    # scoring passes (32-row blocks in the first, 128-row blocks in the second)
+    layout = (("t", 20, -1), ("v", 120, 0), ("t", 30, -1), ("v", 90, 1), ("t", 40, -1))
+    _case(variant(TINY, name="fp_g16", n_layers=2, n_q_heads=16, n_kv_heads=1, head_dim=128, dtype="bf16",
+                  layout=layout, window=32, total_budget=2 * 100, seed=12, score_rows=300))
+
+
+def test_full_prompt_three_query_heads_per_kv_head_d64():
+    # 5 row blocks of 32 rows per pass-A workgroup (15 (head, row block) pairs), head dimension 64
+    layout = (("t", 33, -1), ("v", 200, 0), ("t", 17, -1), ("v", 150, 1), ("t", 50, -1))
+    _case(variant(TINY, name="fp_g3", n_layers=2, n_q_heads=6, n_kv_heads=2, head_dim=64, dtype="bf16",
+                  layout=layout, window=16, total_budget=2 * 120, seed=13, score_rows=450))
 
 
 def test_full_prompt_mid_size_bf16_one_head_per_kv_head():
