@@ -136,6 +136,15 @@ __device__ __forceinline__ void async_copy_wait() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// Tiles filled by these copies cannot pad their rows (a copy instruction writes lane i's 16 bytes at base + 16 i), so
+// the 16-byte chunk c of row r is kept at position c ^ swizzle_of_row(r) of the row: which global chunk a lane
+// fetches is free, and the xor spreads the 16 rows a fragment load touches in one pass over all banks (rows of 256
+// bytes or more start at the same bank: r mod 16; two rows of 128 bytes share a bank line: (r / 2) mod 8).
+template <typename T, int D>
+__device__ __forceinline__ int swizzle_of_row(int r) {
+  return Tile<T, D>::kRowBytes >= 256 ? (r & 15) : ((r >> 1) & 7);
+}
+
 // Copy `rows` consecutive rows (contiguous in global memory) into a padded LDS tile; rows at or
 // beyond `rows_valid` are zero-filled.
 template <typename T, int D>

@@ -193,11 +193,6 @@ constexpr int sim_tiled_lds_bytes() {
 }
 
 template <typename T, int D>
-__device__ __forceinline__ int swizzle_of_row(int r) {
-  return Tile<T, D>::kRowBytes >= 256 ? (r & 15) : ((r >> 1) & 7);
-}
-
-template <typename T, int D>
 __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 ? 2 : 1)) similarity_argmax_kernel(MergeArgs a) {
   using TL = Tile<T, D>;
   constexpr int CPR = TL::kChunksPerRow;

@@ -48,6 +48,16 @@ __global__ void __launch_bounds__(NW * 64, (NW == 8) ? 2 : ((RB == 1 && sizeof(T
   const int cw = wave & 3, rh = wave >> 2;
   const int j0 = tile * kScoreTile;
   const int j = j0 + cw * 32 + n;  // this lane's key column
+  // statistics of row `row` of the launch's (or the block's) rows, head index lh = l * Hq + h
+  auto load_row_stats = [&](const ScoreArgs& a, int lh, int row) {
+    if (BLOCKS) {
+      // planes of stats_rows rows per (layer, head): the bias of the logits, the weights of the cross-modal
+      // probabilities on vision and on text columns (stats_combine_kernel); the probability itself has weight 1
+      const float* plane = reinterpret_cast<const float*>(a.stats) + (size_t)lh * 4 * a.stats_rows + a.stats_row0 + row;
+      return make_float4(plane[0], 1.0f, plane[(size_t)a.stats_rows], plane[2 * (size_t)a.stats_rows]);
+    }
+    return a.stats[(size_t)lh * a.stats_rows + a.stats_row0 + row];
+  };
   auto one_block = [&](const ScoreArgs& a) {
   const bool col_ok = j < a.T;
   const bool col_is_vision = col_ok && a.mask[(size_t)(l / a.Lseq) * a.Tk + j] != 0;
@@ -75,7 +85,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 8) ? 2 : ((RB == 1 && sizeof(T
   qstage.fetch(a.q + ((size_t)(l * a.Hq) * a.q_rows + a.q_row0) * TL::kRowBytes, a.W, tid, NTHR);
   const float4 no_stats = make_float4(0.f, 0.f, 0.f, 0.f);  // rows past the block: zero queries, zero weights
   sreg = no_stats;
-  if (tid < a.W) sreg = a.stats[(size_t)(l * a.Hq) * a.stats_rows + a.stats_row0 + tid];
+  if (tid < a.W) sreg = load_row_stats(a, l * a.Hq, tid);
 
   Frag<T, D> kf;
   float colsum = 0.f;
@@ -116,7 +126,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 8) ? 2 : ((RB == 1 && sizeof(T
       if (KSTAGE && hn % a.G == 0) kstage.template fetch<true>(ktile_src + (size_t)(hn / a.G) * khead_stride, rows_valid, tid, NTHR);
       qstage.fetch(a.q + ((size_t)(l * a.Hq + hn) * a.q_rows + a.q_row0) * TL::kRowBytes, a.W, tid, NTHR);
       sreg = no_stats;
-      if (tid < a.W) sreg = a.stats[(size_t)(l * a.Hq + hn) * a.stats_rows + a.stats_row0 + tid];
+      if (tid < a.W) sreg = load_row_stats(a, l * a.Hq + hn, tid);
     }
     if (hg == 0) {
       frag_load(kf, ktile + (cw * 32 + n) * TL::kStride, kg);
@@ -132,7 +142,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 8) ? 2 : ((RB == 1 && sizeof(T
       int row_min = col_ok ? j - (a.T - a.W) - kg * 4 : (1 << 30);
       int row_end = a.W - kg * 4;
       if (MASKED) asm volatile("" : "+v"(row_min), "+v"(row_end));
-#pragma unroll
+#pragma unroll(BLOCKS ? 1 : RBW)
       for (int rbl = 0; rbl < RBW; ++rbl) {
         const int rb = rh * RBW + rbl;
         Frag<T, D> qf;
@@ -150,7 +160,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 8) ? 2 : ((RB == 1 && sizeof(T
           const float cc[4] = {c4.x, c4.y, c4.z, c4.w};
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            float e = fast_exp2(fmaf(acc[r4 * 4 + i], a.c, -mm[i]));
+            float e = BLOCKS ? fast_exp2((acc[r4 * 4 + i] + mm[i]) * a.c) : fast_exp2(fmaf(acc[r4 * 4 + i], a.c, -mm[i]));
             if (MASKED) e = (rb * 32 + r4 * 8 + i >= row_min && rb * 32 + r4 * 8 + i < row_end) ? e : 0.f;
             colsum = fmaf(e, zz[i], colsum);
             pbar[rbl][r4 * 4 + i] = fmaf(e, cc[i], pbar[rbl][r4 * 4 + i]);
@@ -262,6 +272,7 @@ static hipError_t launch_accum_d(const Plan& p, const ScoreArgs& a, hipStream_t 
 }
 
 hipError_t launch_score_accum(const Plan& p, const Buffers& b, hipStream_t s) {
+  if (score_accum_blocks_supported(p)) return launch_score_accum_blocks(p, b, s);
   const ScoreArgs a = make_args(p, b);
   if (p.dtype == MEDA_BF16) return p.d == 128 ? launch_accum_d<bf16_t, 128>(p, a, s) : launch_accum_d<bf16_t, 64>(p, a, s);
   return p.d == 128 ? launch_accum_d<float, 128>(p, a, s) : launch_accum_d<float, 64>(p, a, s);

@@ -82,4 +82,9 @@ inline ScoreArgs make_args(const Plan& p, const Buffers& b, bool pass_a = false)
   return a;
 }
 
+// Pass B when every prompt row scores, for shapes whose items fit a two-stage LDS ring (score_accum_blocks.hip);
+// the other shapes take the row-block mode of score_accum_kernel.
+bool score_accum_blocks_supported(const Plan& p);
+hipError_t launch_score_accum_blocks(const Plan& p, const Buffers& b, hipStream_t s);
+
 }  // namespace meda

@@ -224,7 +224,21 @@ __global__ void __launch_bounds__(256) stats_combine_kernel(ScoreArgs a) {
   const bool row_is_vision = a.mask[(size_t)(l / a.Lseq) * a.Tk + position] != 0;
   const float coef_v = (!row_is_vision && zv > 0.f) ? 1.0f / zv : 0.f;  // text row: attends to vision columns
   const float coef_t = (row_is_vision && zt > 0.f) ? 1.0f / zt : 0.f;   // vision row: attends to text columns
-  a.stats[idx] = make_float4(M, 1.0f / (zv + zt), coef_v, coef_t);
+  if (a.n_blocks > 1) {
+    // Every prompt row scores: planes of T rows per (layer, head), so that pass B can copy the 128 values of a row
+    // block and a plane as one contiguous piece, and in the form its inner loop wants.  The probability of key j is
+    // exp2(c * (q.k_j + bias)) with bias = -(M + log2 Z) / c, which pass B puts into the accumulators before the
+    // matrix products; the cross-modal probability is that times Z / Z_cross (0 for rows of the wrong modality or
+    // without cross-modal mass).
+    const float z = zv + zt;
+    float* plane = reinterpret_cast<float*>(a.stats) + (size_t)(idx / a.stats_rows) * 4 * a.stats_rows + row;
+    plane[0] = -(M + __log2f(z)) / a.c;
+    plane[(size_t)a.stats_rows] = (!row_is_vision && zv > 1e-30f) ? z / zv : 0.f;     // weight on vision columns
+    plane[2 * (size_t)a.stats_rows] = (row_is_vision && zt > 1e-30f) ? z / zt : 0.f;  // weight on text columns
+    plane[3 * (size_t)a.stats_rows] = 0.f;
+  } else {
+    a.stats[idx] = make_float4(M, 1.0f / (zv + zt), coef_v, coef_t);
+  }
 }
 
 // ------------------------------------------------------------------------------------------ launch

@@ -68,6 +68,14 @@ def test_full_prompt_three_query_heads_per_kv_head_d64():
                   layout=layout, window=16, total_budget=2 * 120, seed=13, score_rows=450))
 
 
+def test_full_prompt_fp32_head_dim_128_takes_the_row_block_mode_of_the_window_kernel():
+    # rows of 512 bytes do not fit the two-stage LDS ring of the dedicated kernel: pass B falls back to the window
+    # kernel walking the row blocks itself; T = 700 = 5 blocks of 128 rows + one of 60
+    layout = (("t", 50, -1), ("v", 250, 0), ("t", 40, -1), ("v", 260, 1), ("t", 100, -1))
+    _case(variant(TINY, name="fp_f32_d128", n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=128, dtype="f32",
+                  layout=layout, window=32, total_budget=2 * 150, seed=17, score_rows=700))
+
+
 def test_full_prompt_mid_size_bf16_one_head_per_kv_head():
     # 16 row blocks, 8 heads without grouping, several layers with different temperatures
     layout = (("t", 40, -1), ("v", 576, 0), ("t", 30, -1), ("v", 576, 1), ("t", 58, -1), ("v", 576, 2), ("t", 192, -1))
