@@ -128,6 +128,11 @@ __device__ __forceinline__ void store16_stream(void* p, const uint4& v) {
 __device__ __forceinline__ void async_copy16_to_lds(const void* gbase, unsigned goff, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(goff), "s"(gbase), "s"(lds_base) : "memory");
 }
+// The same copy with the non-temporal hint: for data that is read once (a stream) and should not push data that
+// other workgroups are about to re-read out of the L2.
+__device__ __forceinline__ void async_copy16_to_lds_stream(const void* gbase, unsigned goff, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(goff), "s"(gbase), "s"(lds_base) : "memory");
+}
 __device__ __forceinline__ void async_copy4_to_lds(const void* gbase, unsigned goff, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(goff), "s"(gbase), "s"(lds_base) : "memory");
 }

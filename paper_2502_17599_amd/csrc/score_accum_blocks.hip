@@ -99,7 +99,7 @@ __global__ void __launch_bounds__(kBlkThreads, 2) score_accum_blocks_kernel(Scor
       // in the first half of the previous kv head, at least one barrier ago.
       const char* ksrc = a.k + (size_t)(l * a.Hkv + g) * a.Tk * RBt;
 #pragma unroll
-      for (int c = 0; c < PF; ++c) async_copy16_to_lds(ksrc, koff[c], lds0 + (unsigned)((wave * PF + c) * 1024));
+      for (int c = 0; c < PF; ++c) async_copy16_to_lds_stream(ksrc, koff[c], lds0 + (unsigned)((wave * PF + c) * 1024));
     }
     const char* qsrc = a.q + (size_t)(l * a.Hq + h) * a.q_rows * RBt;
 #pragma unroll
