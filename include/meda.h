@@ -112,12 +112,12 @@ meda_status meda_compress(const meda_params* params, const void* q_win, const vo
 typedef enum {
   MEDA_REGION_COL_SCORES = 0, /* float [L][Hkv][T]: cumulative attention score A_s (Section 3.3)    */
   MEDA_REGION_INV_NORM = 1,   /* float [L][Hkv][T]: 1/|k| of every key                              */
-  MEDA_REGION_ROW_STATS = 2,  /* float [L][Hq][Wp][4], Wp = W rounded up to 32: log2-domain row max, 1/Z over all
-                                 visible keys, then the row's cross-modal 1/Z as the factor for vision columns
-                                 (text rows, else 0) and for text columns (vision rows, else 0).  With
-                                 MEDA_FLAG_FULL_PROMPT and T > 128: float [L][Hq][4][T], planes of one value per
-                                 position: -(max + log2 Z) / (scale * log2 e), Z / Z_vision (text rows, else
-                                 0), Z / Z_text (vision rows, else 0), unused                           */
+  MEDA_REGION_ROW_STATS = 2,  /* float [L][Hq][4][Wp], Wp = W rounded up to 32: four planes of one value per window
+                                 row: log2-domain row max, 1/Z over all visible keys, then the row's cross-modal
+                                 1/Z as the factor for vision columns (text rows, else 0) and for text columns
+                                 (vision rows, else 0).  With MEDA_FLAG_FULL_PROMPT and T > 128: [L][Hq][4][T],
+                                 one value per position: -(max + log2 Z) / (scale * log2 e), Z / Z_vision (text
+                                 rows, else 0), Z / Z_text (vision rows, else 0), unused                */
   MEDA_REGION_ALLOC = 3,      /* int32 [L][4]: S_l, M_l, N_l, layer of rank l by decreasing S (with n_seqs = N
                                  > 1: [N*L][4], ranks of the sequences interleaved)                  */
   MEDA_REGION_LESS_IDX = 4,   /* int32 ragged: layer l, head g at ((l*T - off[l])*Hkv + g*(T-S_l)): the keys

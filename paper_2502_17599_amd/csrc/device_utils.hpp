@@ -128,6 +128,14 @@ __device__ __forceinline__ void store16_stream(void* p, const uint4& v) {
 __device__ __forceinline__ void async_copy16_to_lds(const void* gbase, unsigned goff, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(goff), "s"(gbase), "s"(lds_base) : "memory");
 }
+// A pointer that is the same in every lane, as a value the compiler knows to be uniform (64-bit address arithmetic
+// is done on the vector unit, and the copies above need their base in scalar registers).
+template <typename P>
+__device__ __forceinline__ const P* uniform_ptr(const P* p) {
+  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return reinterpret_cast<const P*>(((unsigned long long)hi << 32) | lo);
+}
 // The same copy with the non-temporal hint: for data that is read once (a stream) and should not push data that
 // other workgroups are about to re-read out of the L2.
 __device__ __forceinline__ void async_copy16_to_lds_stream(const void* gbase, unsigned goff, unsigned lds_base) {

@@ -50,13 +50,13 @@ __global__ void __launch_bounds__(NW * 64, (NW == 8) ? 2 : ((RB == 1 && sizeof(T
   const int j = j0 + cw * 32 + n;  // this lane's key column
   // statistics of row `row` of the launch's (or the block's) rows, head index lh = l * Hq + h
   auto load_row_stats = [&](const ScoreArgs& a, int lh, int row) {
-    if (BLOCKS) {
-      // planes of stats_rows rows per (layer, head): the bias of the logits, the weights of the cross-modal
-      // probabilities on vision and on text columns (stats_combine_kernel); the probability itself has weight 1
-      const float* plane = reinterpret_cast<const float*>(a.stats) + (size_t)lh * 4 * a.stats_rows + a.stats_row0 + row;
-      return make_float4(plane[0], 1.0f, plane[(size_t)a.stats_rows], plane[2 * (size_t)a.stats_rows]);
-    }
-    return a.stats[(size_t)lh * a.stats_rows + a.stats_row0 + row];
+    // four planes of stats_rows values per (layer, head), written by stats_combine_kernel
+    const float* plane = reinterpret_cast<const float*>(a.stats) + (size_t)lh * 4 * a.stats_rows + a.stats_row0 + row;
+    const size_t ps = (size_t)a.stats_rows;
+    // every prompt row scores: the bias of the logits and the weights of the cross-modal probabilities on vision
+    // and on text columns; the probability itself has weight 1
+    if (BLOCKS) return make_float4(plane[0], 1.0f, plane[ps], plane[2 * ps]);
+    return make_float4(plane[0], plane[ps], plane[2 * ps], plane[3 * ps]);  // maximum, 1/Z, the two cross-modal 1/Z
   };
   auto one_block = [&](const ScoreArgs& a) {
   const bool col_ok = j < a.T;
@@ -273,6 +273,7 @@ static hipError_t launch_accum_d(const Plan& p, const ScoreArgs& a, hipStream_t 
 
 hipError_t launch_score_accum(const Plan& p, const Buffers& b, hipStream_t s) {
   if (score_accum_blocks_supported(p)) return launch_score_accum_blocks(p, b, s);
+  if (score_accum_dma_supported(p)) return launch_score_accum_dma(p, b, s);
   const ScoreArgs a = make_args(p, b);
   if (p.dtype == MEDA_BF16) return p.d == 128 ? launch_accum_d<bf16_t, 128>(p, a, s) : launch_accum_d<bf16_t, 64>(p, a, s);
   return p.d == 128 ? launch_accum_d<float, 128>(p, a, s) : launch_accum_d<float, 64>(p, a, s);

@@ -97,18 +97,18 @@ __global__ void __launch_bounds__(kBlkThreads, 2) score_accum_blocks_kernel(Scor
     if (hf == 0 && h - g * a.G == 0) {
       // The key tile changes with the kv head.  One buffer is enough: every wave took its key fragment out of it
       // in the first half of the previous kv head, at least one barrier ago.
-      const char* ksrc = a.k + (size_t)(l * a.Hkv + g) * a.Tk * RBt;
+      const char* ksrc = uniform_ptr(a.k + (size_t)(l * a.Hkv + g) * a.Tk * RBt);
 #pragma unroll
       for (int c = 0; c < PF; ++c) async_copy16_to_lds_stream(ksrc, koff[c], lds0 + (unsigned)((wave * PF + c) * 1024));
     }
-    const char* qsrc = a.q + (size_t)(l * a.Hq + h) * a.q_rows * RBt;
+    const char* qsrc = uniform_ptr(a.q + (size_t)(l * a.Hq + h) * a.q_rows * RBt);
 #pragma unroll
     for (int c = 0; c < PF; ++c) {
       const unsigned goff = (unsigned)min(pos0 + crow + c * RPI, a.Tk - 1) * RBt + qchunk[c];
       async_copy16_to_lds(qsrc, goff, stage + (unsigned)((wave * PF + c) * 1024));
     }
     // wave w brings the rows (w & 1) * 64 .. + 63 of plane w >> 1 of the row statistics
-    const float* ssrc = stats_f + ((size_t)(l * a.Hq + h) * 4 + (wave >> 1)) * a.stats_rows;
+    const float* ssrc = uniform_ptr(stats_f + ((size_t)(l * a.Hq + h) * 4 + (wave >> 1)) * a.stats_rows);
     const unsigned soff = (unsigned)min(pos0 + (wave & 1) * 64 + lane, a.Tk - 1) * 4u;
     async_copy4_to_lds(ssrc, soff, stage + (unsigned)(kTileBytes + ((wave >> 1) * kBlkHalf + (wave & 1) * 64) * 4));
   };

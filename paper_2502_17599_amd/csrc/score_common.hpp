@@ -26,7 +26,8 @@ struct ScoreArgs {
   const char* k;
   const uint8_t* mask;  // [N][Tk]: layer l belongs to sequence l / Lseq
   float4* stats_part;  // [L][Hq][Wp][NPART] (max, Z_vision, Z_text, -)
-  float4* stats;       // [L][Hq][Wp]        (max, 1/Z_all, coef for vision columns, coef for text columns)
+  float4* stats;       // [L][Hq][4][stats_rows] floats: planes of (max, 1/Z_all, coef for vision columns, coef for text
+                       // columns), or of their full-prompt form (stats_combine_kernel)
   float* inv_norm;     // [L][Hkv][T]
   float* col_scores;   // [L][Hkv][T]
   double* ent_part;    // [L][NT][2]
@@ -86,5 +87,10 @@ inline ScoreArgs make_args(const Plan& p, const Buffers& b, bool pass_a = false)
 // the other shapes take the row-block mode of score_accum_kernel.
 bool score_accum_blocks_supported(const Plan& p);
 hipError_t launch_score_accum_blocks(const Plan& p, const Buffers& b, hipStream_t s);
+
+// Pass B of the window mode for grouped heads, fed by asynchronous copies (score_accum_dma.hip); bit-identical
+// results to score_accum_kernel, which keeps the other shapes.
+bool score_accum_dma_supported(const Plan& p);
+hipError_t launch_score_accum_dma(const Plan& p, const Buffers& b, hipStream_t s);
 
 }  // namespace meda

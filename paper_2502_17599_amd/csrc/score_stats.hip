@@ -12,12 +12,23 @@ namespace meda {
 // every tile of its chunk.  The product is taken with the keys as operand A and the queries as
 // operand B, so a lane owns one query row and 16 keys per block: the running (max, Z_vision, Z_text)
 // of the row live in three registers per fragment and need no cross-lane traffic until the end.
-template <typename T, int D, int NQ, int NW, bool BLOCKS>
+//
+// Two ways of bringing the key tiles into LDS.  Through registers (DMA false): the next tile is fetched into registers
+// while the current one is processed, and written to a padded LDS tile between two barriers.  By asynchronous
+// global-to-LDS copies (DMA true, rows of at most 256 bytes): two unpadded, xor-swizzled tiles (swizzle_of_row in
+// device_utils.hpp); the copies of tile t+1 are issued when tile t starts, one wait and one barrier per tile, no
+// staging registers; the modality bits of a tile's keys are ballots of two bytes per lane that every wave loads for
+// itself one tile ahead.  The arithmetic is the same instruction for instruction, so the results are bit-identical.
+template <typename T, int D, int NQ, int NW, bool BLOCKS, bool DMA>
 __global__ void __launch_bounds__(NW * 64, (NQ == 1 && NW == 4 && sizeof(T) == 2) ? 3 : 2) score_stats_kernel(ScoreArgs a) {
   using TL = Tile<T, D>;
+  constexpr int RBt = TL::kRowBytes;
+  constexpr int CPR = TL::kChunksPerRow;
+  constexpr int NC = TL::kFragChunks;
+  constexpr int kTileBytes = kScoreTile * RBt;
   extern __shared__ __align__(16) char smem[];
   char* ktile = smem;
-  uint8_t* lmask = reinterpret_cast<uint8_t*>(smem + kScoreTile * TL::kStride);
+  uint8_t* lmask = reinterpret_cast<uint8_t*>(smem + kScoreTile * TL::kStride);  // (DMA false)
 
   const int ch = blockIdx.x, l = blockIdx.z;
   int g = blockIdx.y, bi = 0;
@@ -70,30 +81,75 @@ __global__ void __launch_bounds__(NW * 64, (NQ == 1 && NW == 4 && sizeof(T) == 2
   const char* kbase = a.k + (size_t)(l * a.Hkv + g) * a.Tk * TL::kRowBytes;
   float* invn_out = a.inv_norm + (size_t)(l * a.Hkv + g) * a.Tk;
 
-  TileStage<T, D, kScoreTile, nthr> stage;
+  TileStage<T, D, DMA ? 1 : kScoreTile, nthr> stage;
   uint8_t mreg = 0;
-  if (jbeg < jend) {
+  // DMA: copy instruction c of this wave fills the rows (wave * PF + c) * RPI .. + RPI-1 of a tile, this lane brings
+  // one 16-byte chunk; rows past the end of the sequence repeat the last key (their columns are masked below)
+  constexpr int RPI = 64 / CPR;
+  constexpr int PF = DMA ? kScoreTile / RPI / NW : 1;
+  static_assert(!DMA || (64 % CPR == 0 && kScoreTile % (RPI * NW) == 0), "the copy instructions must tile a tile evenly");
+  unsigned crow[PF], cchunk[PF], coff[NC];
+  uint8_t mk0 = 0, mk1 = 0;            // modality bytes of the keys lane and 64 + lane of the next tile
+  unsigned long long cur0 = 0, cur1 = 0;  // modality bits of the current tile's keys 0..63 and 64..127
+  const unsigned lds0 = (unsigned)(size_t)smem;
+  const char* kbase_u = uniform_ptr(kbase);
+  auto issue = [&](int jt, int slot) {
+#pragma unroll
+    for (int c = 0; c < PF; ++c)
+      async_copy16_to_lds_stream(kbase_u, (unsigned)min(jt + (int)crow[c], a.T - 1) * RBt + cchunk[c],
+                                 lds0 + (unsigned)(slot * kTileBytes + (wave * PF + c) * 1024));
+    mk0 = (jt + lane < a.T) ? mask[jt + lane] : 0;
+    mk1 = (jt + 64 + lane < a.T) ? mask[jt + 64 + lane] : 0;
+  };
+  if (DMA) {
+#pragma unroll
+    for (int c = 0; c < PF; ++c) {
+      crow[c] = (unsigned)((wave * PF + c) * RPI + lane / CPR);
+      cchunk[c] = (unsigned)(((lane % CPR) ^ swizzle_of_row<T, D>((int)crow[c])) * 16);
+    }
+    // chunk c of this lane's fragment (chunk kg * NC + c of row n of a 32-row block)
+#pragma unroll
+    for (int c = 0; c < NC; ++c) coff[c] = (unsigned)(n * RBt + (((kg * NC + c) ^ swizzle_of_row<T, D>(n)) * 16));
+    if (jbeg < jend) issue(jbeg, 0);
+  } else if (jbeg < jend) {
     stage.template fetch<true>(kbase + (size_t)jbeg * TL::kRowBytes, min(kScoreTile, a.T - jbeg), tid, nthr);
     if (tid < kScoreTile) mreg = (jbeg + tid < a.T) ? mask[jbeg + tid] : 0;
   }
-  for (int j0 = jbeg; j0 < jend; j0 += kScoreTile) {
-    __syncthreads();  // the previous tile is no longer read
+  int slot = 0;
+  for (int j0 = jbeg; j0 < jend; j0 += kScoreTile, slot ^= 1) {
     const int rows_valid = min(kScoreTile, a.T - j0);
-    stage.commit(ktile, tid, nthr);
-    if (tid < kScoreTile) lmask[tid] = mreg;
-    __syncthreads();
-    if (j0 + kScoreTile < jend) {  // next tile's loads are in flight while this one is processed
-      const int jn = j0 + kScoreTile;
-      stage.template fetch<true>(kbase + (size_t)jn * TL::kRowBytes, min(kScoreTile, a.T - jn), tid, nthr);
-      if (tid < kScoreTile) mreg = (jn + tid < a.T) ? mask[jn + tid] : 0;
+    if (DMA) {
+      async_copy_wait<0>();  // this wave's pieces of the tile have landed
+      __syncthreads();       // every wave's have; and nobody reads the other tile (the previous one) any more
+      cur0 = __ballot(mk0 != 0);
+      cur1 = __ballot(mk1 != 0);
+      if (j0 + kScoreTile < jend) issue(j0 + kScoreTile, slot ^ 1);
+      ktile = smem + slot * kTileBytes;
+    } else {
+      __syncthreads();  // the previous tile is no longer read
+      stage.commit(ktile, tid, nthr);
+      if (tid < kScoreTile) lmask[tid] = mreg;
+      __syncthreads();
+      if (j0 + kScoreTile < jend) {  // next tile's loads are in flight while this one is processed
+        const int jn = j0 + kScoreTile;
+        stage.template fetch<true>(kbase + (size_t)jn * TL::kRowBytes, min(kScoreTile, a.T - jn), tid, nthr);
+        if (tid < kScoreTile) mreg = (jn + tid < a.T) ? mask[jn + tid] : 0;
+      }
     }
 
     // 1/|k| of the tile's keys: two threads per row (the first row block sees every key; the others skip this)
     for (int row = tid >> 1; bi == 0 && row < kScoreTile; row += nthr >> 1) {
-      const uint4* p = reinterpret_cast<const uint4*>(ktile + row * TL::kStride + (tid & 1) * TL::kHalfBytes);
       float ss = 0.f;
+      if (DMA) {
 #pragma unroll
-      for (int i = 0; i < TL::kFragChunks; ++i) ss += chunk_sumsq<T>(p[i]);
+        for (int i = 0; i < NC; ++i)
+          ss += chunk_sumsq<T>(*reinterpret_cast<const uint4*>(
+              ktile + row * RBt + ((((tid & 1) * NC + i) ^ swizzle_of_row<T, D>(row)) * 16)));
+      } else {
+        const uint4* p = reinterpret_cast<const uint4*>(ktile + row * TL::kStride + (tid & 1) * TL::kHalfBytes);
+#pragma unroll
+        for (int i = 0; i < NC; ++i) ss += chunk_sumsq<T>(p[i]);
+      }
       ss += __shfl_xor(ss, 1, kWave);
       if ((tid & 1) == 0 && row < rows_valid) invn_out[j0 + row] = 1.0f / fmaxf(sqrtf(ss), 1e-30f);
     }
@@ -102,8 +158,15 @@ __global__ void __launch_bounds__(NW * 64, (NQ == 1 && NW == 4 && sizeof(T) == 2
       const int jb = j0 + sb * 32;
       if (jb >= a.T || (BLOCKS && jb > wave_last)) break;  // past the sequence, or past every row of this wave
       Frag<T, D> kf;
-      frag_load(kf, ktile + (sb * 32 + n) * TL::kStride, kg);
-      const uint32_t mword = (uint32_t)__ballot(lmask[sb * 32 + n] != 0);
+      uint32_t mword;
+      if (DMA) {
+#pragma unroll
+        for (int c = 0; c < NC; ++c) kf.c[c] = *reinterpret_cast<const uint4*>(ktile + sb * 32 * RBt + coff[c]);
+        mword = (uint32_t)((sb & 2 ? cur1 : cur0) >> ((sb & 1) * 32));
+      } else {
+        frag_load(kf, ktile + (sb * 32 + n) * TL::kStride, kg);
+        mword = (uint32_t)__ballot(lmask[sb * 32 + n] != 0);
+      }
       const bool tail = jb + 31 >= a.T;  // the block runs past the end of the sequence
       const bool one_modality = mword == 0u || mword == 0xffffffffu;
       const bool full_all = jb + 31 <= a.T - a.W;  // every key of the block is visible to every row of the window
@@ -204,8 +267,9 @@ __global__ void __launch_bounds__(256) stats_combine_kernel(ScoreArgs a) {
   if (a.n_blocks > 1) {
     position = row;  // one chunk of keys per row block: every partial of the row exists
   } else {
-    if (row >= a.W) {
-      a.stats[idx] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (row >= a.W) {  // padding rows of the window: no weight
+      float* plane = reinterpret_cast<float*>(a.stats) + (size_t)(idx / a.stats_rows) * 4 * a.stats_rows + row;
+      plane[0] = plane[(size_t)a.stats_rows] = plane[2 * (size_t)a.stats_rows] = plane[3 * (size_t)a.stats_rows] = 0.f;
       return;
     }
     position = a.T - a.W + row;
@@ -225,8 +289,9 @@ __global__ void __launch_bounds__(256) stats_combine_kernel(ScoreArgs a) {
   const float coef_v = (!row_is_vision && zv > 0.f) ? 1.0f / zv : 0.f;  // text row: attends to vision columns
   const float coef_t = (row_is_vision && zt > 0.f) ? 1.0f / zt : 0.f;   // vision row: attends to text columns
   if (a.n_blocks > 1) {
-    // Every prompt row scores: planes of T rows per (layer, head), so that pass B can copy the 128 values of a row
-    // block and a plane as one contiguous piece, and in the form its inner loop wants.  The probability of key j is
+    // The statistics are stored as four planes of stats_rows values per (layer, head), so that pass B can copy the
+    // values of a row block and a plane as one contiguous piece.  Every prompt row scores: the planes hold the form
+    // the inner loop of that mode wants.  The probability of key j is
     // exp2(c * (q.k_j + bias)) with bias = -(M + log2 Z) / c, which pass B puts into the accumulators before the
     // matrix products; the cross-modal probability is that times Z / Z_cross (0 for rows of the wrong modality or
     // without cross-modal mass).
@@ -237,16 +302,21 @@ __global__ void __launch_bounds__(256) stats_combine_kernel(ScoreArgs a) {
     plane[2 * (size_t)a.stats_rows] = (row_is_vision && zt > 1e-30f) ? z / zt : 0.f;  // weight on text columns
     plane[3 * (size_t)a.stats_rows] = 0.f;
   } else {
-    a.stats[idx] = make_float4(M, 1.0f / (zv + zt), coef_v, coef_t);
+    // the window: row maximum, 1/Z, and the cross-modal 1/Z as the weight on vision and on text columns
+    float* plane = reinterpret_cast<float*>(a.stats) + (size_t)(idx / a.stats_rows) * 4 * a.stats_rows + row;
+    plane[0] = M;
+    plane[(size_t)a.stats_rows] = 1.0f / (zv + zt);
+    plane[2 * (size_t)a.stats_rows] = coef_v;
+    plane[3 * (size_t)a.stats_rows] = coef_t;
   }
 }
 
 // ------------------------------------------------------------------------------------------ launch
 
-template <typename T, int D, int NQ, int NW, bool BLOCKS>
+template <typename T, int D, int NQ, int NW, bool BLOCKS, bool DMA>
 static hipError_t launch_stats_b(const Plan& p, const ScoreArgs& a, hipStream_t s) {
-  const size_t lds = (size_t)kScoreTile * Tile<T, D>::kStride + kScoreTile;
-  auto kern = score_stats_kernel<T, D, NQ, NW, BLOCKS>;
+  const size_t lds = DMA ? 2 * (size_t)kScoreTile * Tile<T, D>::kRowBytes : (size_t)kScoreTile * Tile<T, D>::kStride + kScoreTile;
+  auto kern = score_stats_kernel<T, D, NQ, NW, BLOCKS, DMA>;
   if (lds > 64 * 1024) {
     hipError_t e = allow_dynamic_lds(kern, (int)lds);
     if (e != hipSuccess) return e;
@@ -258,7 +328,15 @@ static hipError_t launch_stats_b(const Plan& p, const ScoreArgs& a, hipStream_t 
 
 template <typename T, int D, int NQ, int NW>
 static hipError_t launch_stats_w(const Plan& p, const ScoreArgs& a, hipStream_t s) {
-  return p.n_blocks > 1 ? launch_stats_b<T, D, NQ, NW, true>(p, a, s) : launch_stats_b<T, D, NQ, NW, false>(p, a, s);
+  // Asynchronous copies where the pass is not already at the memory's rate: grouped heads, and every prompt row
+  // scoring.  With one query head per kv head and a window of 32 rows the pass streams the keys at the rate a plain
+  // read reaches, and three workgroups per CU of the small register-staged form do that best.
+  constexpr bool kCanDma = Tile<T, D>::kRowBytes <= 256;
+  if constexpr (kCanDma) {
+    if (p.n_blocks > 1) return launch_stats_b<T, D, NQ, NW, true, true>(p, a, s);
+    if (p.G >= 2) return launch_stats_b<T, D, NQ, NW, false, true>(p, a, s);
+  }
+  return p.n_blocks > 1 ? launch_stats_b<T, D, NQ, NW, true, false>(p, a, s) : launch_stats_b<T, D, NQ, NW, false, false>(p, a, s);
 }
 
 template <typename T, int D, int NQ>
