@@ -49,7 +49,8 @@ __device__ __forceinline__ int sort_passes(int S) {
 constexpr int kResWaves = 8;
 constexpr int kResThreads = kResWaves * 64;
 constexpr int kResLdsBytes = 160 * 1024;
-constexpr int kResSplit = 1;  // 2 and 3 parts per pair (more, shorter workgroups) measured slower
+constexpr int kResSplit = 1;  // 2 and 3 parts per pair (more, shorter workgroups) measured slower; so did giving this
+                             // kernel only as many layers as fill whole rounds of one workgroup per CU
 
 // conserved keys (a multiple of 32) that fit: one padded row and one 1/|k| each
 template <typename T, int D>
