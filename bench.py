@@ -25,10 +25,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 HEADLINE = "extreme"
-# kernels a phase launches
+# kernels a phase launches (score_accum: one of the three, by the shape: grouped heads take the _dma form, the
+# full-prompt mode the _blocks form; similarity: the packing kernel, then the tiled and the resident-set kernel)
 PHASE_KERNELS = {"score_stats": ["score_stats_kernel"], "stats_combine": ["stats_combine_kernel"],
-                 "score_accum": ["score_accum_kernel"], "allocate": ["allocate_kernel"], "select": ["select_kernel"],
-                 "similarity": ["similarity_argmax_kernel", "similarity_resident_kernel"],
+                 "score_accum": ["score_accum_kernel | score_accum_dma_kernel | score_accum_blocks_kernel"],
+                 "allocate": ["allocate_kernel"], "select": ["select_kernel"],
+                 "similarity": ["pack_conserved_kernel", "similarity_argmax_kernel", "similarity_resident_kernel"],
                  "segment_sort": ["segment_sort_kernel"], "merge_write": ["merge_write_kernel"]}
 PHASE_BOUND = {"score_stats": "hbm", "score_accum": "hbm", "similarity": "mfma", "merge_write": "hbm",
                "select": "hbm", "segment_sort": "hbm", "stats_combine": "hbm", "allocate": "hbm"}
