@@ -34,7 +34,7 @@ typedef enum {
   MEDA_OK = 0,
   MEDA_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, Hq % Hkv != 0, window > seq_len ...  */
   MEDA_ERR_BUDGET = 2,      /* total_budget outside [L*min(W,T), L*T]                               */
-  MEDA_ERR_UNSUPPORTED = 3, /* head_dim / dtype / window / group size outside the built set         */
+  MEDA_ERR_UNSUPPORTED = 3, /* head_dim / dtype / group size (Hq / Hkv > 32) / sizes outside the built set */
   MEDA_ERR_WORKSPACE = 4,   /* workspace null, misaligned or smaller than meda_workspace_bytes()    */
   MEDA_ERR_HIP = 5,         /* a HIP call or kernel launch failed                                    */
   MEDA_ERR_SCRATCH_LIMIT = 6 /* meda_decode_attention_noalloc: the step needs more scratch than the
@@ -57,7 +57,7 @@ typedef struct {
   int32_t n_kv_heads;   /* Hkv, Hq % Hkv == 0; query head h reads kv head h / (Hq/Hkv)             */
   int32_t head_dim;     /* d: 64 or 128                                                            */
   int32_t seq_len;      /* T: cached positions per layer                                           */
-  int32_t window;       /* W: rows of q_win = the last W positions, 1 <= W <= min(T, 128)          */
+  int32_t window;       /* W: rows of q_win = the last W positions, 1 <= W <= T                      */
   int64_t total_budget; /* B = sum_l S_l, kept positions per kv head summed over layers            */
   int32_t recent_num;   /* M_l = max(min(W,S_l), floor(S_l*num/den)); 3/4 is the paper's 3:1 split */
   int32_t recent_den;   /*   (Section 4.3); den > 0, 0 <= num <= den                               */
@@ -115,8 +115,8 @@ typedef enum {
   MEDA_REGION_ROW_STATS = 2,  /* float [L][Hq][4][Wp], Wp = W rounded up to 32: four planes of one value per window
                                  row: log2-domain row max, 1/Z over all visible keys, then the row's cross-modal
                                  1/Z as the factor for vision columns (text rows, else 0) and for text columns
-                                 (vision rows, else 0).  With MEDA_FLAG_FULL_PROMPT and T > 128: [L][Hq][4][T],
-                                 one value per position: -(max + log2 Z) / (scale * log2 e), Z / Z_vision (text
+                                 (vision rows, else 0).  With more than 128 scoring rows R (W, or T with
+                                 MEDA_FLAG_FULL_PROMPT): [L][Hq][4][R], one value per row: -(max + log2 Z) / (scale * log2 e), Z / Z_vision (text
                                  rows, else 0), Z / Z_text (vision rows, else 0), unused                */
   MEDA_REGION_ALLOC = 3,      /* int32 [L][4]: S_l, M_l, N_l, layer of rank l by decreasing S (with n_seqs = N
                                  > 1: [N*L][4], ranks of the sequences interleaved)                  */

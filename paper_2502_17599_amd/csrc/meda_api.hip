@@ -14,7 +14,7 @@ static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // Tiling of the two scoring passes for w query rows (the last w positions) of a sequence of t keys.  With
 // `single_chunk` a pass-A workgroup walks all keys its rows see (used when every prompt row scores: the row blocks
 // already give that launch tens of thousands of workgroups).
-static bool score_geometry(Plan* pl, int t, int w, bool single_chunk) {
+static bool score_geometry(Plan* pl, int t, int w, int rows, bool single_chunk) {
   pl->Tb = t;
   pl->Wb = w;
   pl->RB = (w + 31) / 32;
@@ -25,11 +25,11 @@ static bool score_geometry(Plan* pl, int t, int w, bool single_chunk) {
   pl->RBa = pl->RB;
   if (single_chunk) {
     const int want = pl->G >= 16 ? 1 : 16 / pl->G;
-    const int have = (t + 31) / 32;
+    const int have = (rows + 31) / 32;
     pl->RBa = want < have ? want : have;
   }
   pl->row_block_a = pl->RBa * 32;
-  pl->n_blocks_a = single_chunk ? (t + pl->row_block_a - 1) / pl->row_block_a : 1;
+  pl->n_blocks_a = single_chunk ? (rows + pl->row_block_a - 1) / pl->row_block_a : 1;
   const int combos = pl->G * pl->RBa;
   if (combos > 32 || pl->RB > 4) return false;
   pl->NQ = combos <= 4 ? 1 : (combos <= 16 ? 2 : 4);  // (head, row block) pairs a wave keeps in registers
@@ -61,7 +61,7 @@ meda_status make_plan(const meda_params* p, Plan* out) {
   if (p->n_seqs < 0) return MEDA_ERR_INVALID_ARG;
   const int n_seqs = p->n_seqs > 0 ? p->n_seqs : 1;
   const int64_t layers = (int64_t)n_seqs * p->n_layers;  // layers of the whole batch
-  if (layers > kMaxLayers || p->window > 128) return MEDA_ERR_UNSUPPORTED;
+  if (layers > kMaxLayers) return MEDA_ERR_UNSUPPORTED;
   if (layers * p->n_kv_heads * (int64_t)p->seq_len >= (1ll << 31)) return MEDA_ERR_UNSUPPORTED;
   if (layers * p->n_q_heads * 128 >= (1ll << 31)) return MEDA_ERR_UNSUPPORTED;
   {
@@ -82,16 +82,17 @@ meda_status make_plan(const meda_params* p, Plan* out) {
 
   const bool full_prompt = (pl.flags & MEDA_FLAG_FULL_PROMPT) != 0;
   pl.R = full_prompt ? pl.T : pl.W;
-  pl.n_blocks = full_prompt ? (pl.T + kScoreRowBlock - 1) / kScoreRowBlock : 1;
+  // More than 128 scoring rows (a long observation window, or every prompt row), or more (head, 32-row block) pairs
+  // per kv head than a workgroup of the window kernels holds: the rows are cut into row blocks counted from the end,
+  // and one launch of each scoring kernel covers all of them.
+  pl.blocks = (pl.R > kScoreRowBlock || pl.G * ((pl.R + 31) / 32) > 32) ? 1 : 0;
   pl.Tk = pl.T;
   pl.q_row0 = 0;
   pl.NTk = (pl.T + kScoreTile - 1) / kScoreTile;
   pl.accumulate = 0;
-  // Scoring geometry.  With every prompt row scoring, one launch of each scoring kernel covers all row blocks
-  // (the kernels derive a block's key count and rows themselves) and the row statistics hold all R = T rows.
-  const int w_score = full_prompt ? (pl.T < kScoreRowBlock ? pl.T : kScoreRowBlock) : pl.W;
-  if (!score_geometry(&pl, pl.T, w_score, pl.n_blocks > 1)) return MEDA_ERR_UNSUPPORTED;
-  const size_t stats_rows = pl.n_blocks > 1 ? (size_t)pl.R : (size_t)pl.Wp;
+  const int w_score = (pl.blocks || pl.R > kScoreRowBlock) ? kScoreRowBlock : pl.R;
+  if (!score_geometry(&pl, pl.T, w_score, pl.R, pl.blocks)) return MEDA_ERR_UNSUPPORTED;
+  const size_t stats_rows = pl.blocks ? (size_t)pl.R : (size_t)pl.Wp;
 
   pl.n_less_total = (size_t)((int64_t)pl.L * pl.T - pl.B) * pl.Hkv;
   size_t o = 0;
@@ -190,7 +191,7 @@ meda_status meda_workspace_region(const meda_params* params, int region, size_t*
     case MEDA_REGION_INV_NORM: *offset = pl.off_inv_norm; *bytes = (size_t)pl.L * pl.Hkv * pl.T * 4; break;
     case MEDA_REGION_ROW_STATS:
       *offset = pl.off_stats;
-      *bytes = (size_t)pl.L * pl.Hq * (pl.n_blocks > 1 ? (size_t)pl.R : (size_t)pl.Wp) * 16;
+      *bytes = (size_t)pl.L * pl.Hq * (pl.blocks ? (size_t)pl.R : (size_t)pl.Wp) * 16;
       break;
     case MEDA_REGION_ALLOC: *offset = pl.off_alloc; *bytes = (size_t)pl.L * 16; break;
     case MEDA_REGION_LESS_IDX: *offset = pl.off_less_idx; *bytes = pl.n_less_total * 4; break;

@@ -35,13 +35,14 @@ struct Plan {
   int NQ, NCG, CS;   // pass A: (head, row block) pairs per wave, wave groups, column split
   int CH, NCH, NPART;  // pass A: columns per chunk, chunks, partial statistics per row
   int NT;            // pass B: column tiles
-  // Scoring rows.  Normally the W window rows (R == W).  With MEDA_FLAG_FULL_PROMPT every prompt position
-  // scores (R == T): the rows are cut into n_blocks blocks of at most kScoreRowBlock rows counted from the end; a
-  // block of rows [Tb - Wb, Tb) sees only the keys below Tb, so it is the window computation of a sequence cut
-  // after its last row.  One launch of each scoring kernel covers all blocks (the kernels derive Tb, Wb themselves).
-  int Tb, Wb;        // keys and query rows of the scoring launch (T and W; with the flag: T and the block size)
+  // Scoring rows: the W window rows (R == W), or with MEDA_FLAG_FULL_PROMPT every prompt position (R == T); they are
+  // the last R positions.  In the row-block mode (`blocks`: R > 128, or more (head, 32-row block) pairs per kv head
+  // than the window kernels hold) the rows are cut into blocks counted from the end; a block of the positions
+  // [Tb - Wb, Tb) sees only the keys below Tb, so it is the window computation of a sequence cut after its last row.
+  // One launch of each scoring kernel covers all blocks (the kernels derive Tb, Wb themselves).
+  int Tb, Wb;        // keys and query rows of the scoring launch (T and W; in the row-block mode: T and 128)
   int R;             // scoring rows in total; rows per (layer, head) in the query buffer
-  int n_blocks;      // row blocks
+  int blocks;        // row-block mode
   int Tk;            // key rows per (layer, kv head) in memory (T of the whole sequence)
   int q_row0;        // first row of the block inside the query buffer
   int NTk;           // column tiles of the whole sequence (stride of the per-tile entropy partials)

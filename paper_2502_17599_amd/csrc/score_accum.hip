@@ -35,7 +35,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 8) ? 2 : ((RB == 1 && sizeof(T
   // memory-side cache) are the first ones read here
   int tile = blockIdx.x, l = a0.L - 1 - blockIdx.y;
   if (BLOCKS) {
-    // Every prompt row scores: the workgroup takes its column tile through ALL row blocks that see it (block bi
+    // Row-block mode (more than 128 scoring rows): the workgroup takes its column tile through ALL row blocks that see it (block bi
     // sees the tile iff j0 < Tk - bi * row_block), one after the other: one writer per column and entropy partial,
     // in a fixed order, so the sums do not depend on the launch.  Tile t is seen by NT - t row blocks: the longest
     // workgroups go first (tile 0 of all layers, then tile 1, ...).  (Giving a workgroup the tiles t and NT-1-t, and
@@ -220,7 +220,8 @@ __global__ void __launch_bounds__(NW * 64, (NW == 8) ? 2 : ((RB == 1 && sizeof(T
   if (!BLOCKS) {
     one_block(a0);
   } else {
-    const int n_bi = (a0.Tk - j0 + a0.row_block - 1) / a0.row_block;
+    // row blocks that exist and see this tile
+    const int n_bi = min((a0.Tk - j0 + a0.row_block - 1) / a0.row_block, (a0.q_rows + a0.row_block - 1) / a0.row_block);
     for (int bi = 0; bi < n_bi; ++bi) {
       ScoreArgs a = a0;
       select_row_block(a, bi);
@@ -252,7 +253,7 @@ static hipError_t launch_accum_t(const Plan& p, const ScoreArgs& a, hipStream_t 
   constexpr bool kThreeGroups = RB == 1 && sizeof(T) == 2;
   constexpr int NW = RB == 4 ? 8 : 4;  // four row blocks: two row groups of two (measured: no gain for two row blocks)
   if constexpr (RB == kScoreRowBlock / 32) {
-    if (p.n_blocks > 1) {  // every prompt row scores: row blocks walked inside the kernel
+    if (p.blocks) {  // row-block mode: row blocks walked inside the kernel
       if (p.G == 1) return launch_accum_k<T, D, RB, true, NW, true>(p, a, s);
       return launch_accum_k<T, D, RB, false, NW, true>(p, a, s);
     }

@@ -1,5 +1,6 @@
-// Pass B of the scoring when every prompt row scores (Sections 3.2 and 3.3 as the paper writes them: the column
-// scores sum A_p over all prompt rows, the cross-modal matrices take all text / vision queries).  Same arithmetic as
+// Pass B of the scoring in the row-block mode: more than 128 scoring rows, that is a long observation window or every
+// prompt row (Sections 3.2 and 3.3 as the paper writes them: the column scores sum A_p over all prompt rows, the
+// cross-modal matrices take all text / vision queries).  Same arithmetic as
 // score_accum_kernel in its row-block mode, other data movement: the work of a workgroup is a long sequence of
 // (row block, query head) items against one column tile of 128 keys, and what limits it is how the key tile, the
 // query rows and the row statistics of an item get into LDS.  Here they come by asynchronous global-to-LDS copies:
@@ -67,7 +68,8 @@ __global__ void __launch_bounds__(kBlkThreads, 2) score_accum_blocks_kernel(Scor
   const int j = j0 + cw * 32 + n;  // this lane's key column
   const bool col_is_vision = j < a.Tk && a.mask[(size_t)(l / a.Lseq) * a.Tk + j] != 0;
   const int coef_plane = col_is_vision ? 1 : 2;  // text rows weigh vision columns, vision rows text columns
-  const int n_bi = (a.Tk - j0 + kBlkRows - 1) / kBlkRows;  // row blocks that see this tile
+  // row blocks that exist (the scoring rows are the last q_rows positions) and see this tile
+  const int n_bi = min((a.Tk - j0 + kBlkRows - 1) / kBlkRows, (a.q_rows + kBlkRows - 1) / kBlkRows);
   const int n_items = n_bi * a.Hq * 2;                     // (row block, head, half), the half running fastest
 
   for (int i = tid; i < a.Hkv * kScoreTile; i += kBlkThreads) colacc[i] = 0.f;  // published by the first barrier
@@ -86,13 +88,15 @@ __global__ void __launch_bounds__(kBlkThreads, 2) score_accum_blocks_kernel(Scor
   }
   const unsigned lds0 = (unsigned)(size_t)smem;
   const float* stats_f = reinterpret_cast<const float*>(a.stats);
-  // Row block bi holds the rows [Tb - Wb, Tb), Tb = Tk - bi * 256, Wb = min(256, Tb); half hf of it starts at the
-  // position Tb - Wb + hf * 128 (the last block may leave the second half short or empty: its rows are masked).
+  // Row block bi holds the positions [Tb - Wb, Tb), Tb = Tk - bi * 256, Wb = min(256, q_rows - bi * 256): the scoring
+  // rows are the last q_rows positions, row r of the query and statistics buffers is the position Tk - q_rows + r.
+  // Half hf of a block starts at the position Tb - Wb + hf * 128 (the last block may leave the second half short or
+  // empty: its rows are masked).
   auto issue = [&](int item) {
     const int hf = item & 1, hh = item >> 1;
     const int bi = hh / a.Hq, h = hh - bi * a.Hq;
     const int g = h / a.G;
-    const int Tb = a.Tk - bi * kBlkRows, pos0 = Tb - min(kBlkRows, Tb) + hf * kBlkHalf;
+    const int row0 = a.q_rows - bi * kBlkRows - min(kBlkRows, a.q_rows - bi * kBlkRows) + hf * kBlkHalf;  // in the buffers
     const unsigned stage = lds0 + (unsigned)(kTileBytes + (item & 1) * kStageBytes);
     if (hf == 0 && h - g * a.G == 0) {
       // The key tile changes with the kv head.  One buffer is enough: every wave took its key fragment out of it
@@ -104,12 +108,12 @@ __global__ void __launch_bounds__(kBlkThreads, 2) score_accum_blocks_kernel(Scor
     const char* qsrc = uniform_ptr(a.q + (size_t)(l * a.Hq + h) * a.q_rows * RBt);
 #pragma unroll
     for (int c = 0; c < PF; ++c) {
-      const unsigned goff = (unsigned)min(pos0 + crow + c * RPI, a.Tk - 1) * RBt + qchunk[c];
+      const unsigned goff = (unsigned)min(row0 + crow + c * RPI, a.q_rows - 1) * RBt + qchunk[c];
       async_copy16_to_lds(qsrc, goff, stage + (unsigned)((wave * PF + c) * 1024));
     }
     // wave w brings the rows (w & 1) * 64 .. + 63 of plane w >> 1 of the row statistics
     const float* ssrc = uniform_ptr(stats_f + ((size_t)(l * a.Hq + h) * 4 + (wave >> 1)) * a.stats_rows);
-    const unsigned soff = (unsigned)min(pos0 + (wave & 1) * 64 + lane, a.Tk - 1) * 4u;
+    const unsigned soff = (unsigned)min(row0 + (wave & 1) * 64 + lane, a.q_rows - 1) * 4u;
     async_copy4_to_lds(ssrc, soff, stage + (unsigned)(kTileBytes + ((wave >> 1) * kBlkHalf + (wave & 1) * 64) * 4));
   };
 
@@ -153,7 +157,7 @@ __global__ void __launch_bounds__(kBlkThreads, 2) score_accum_blocks_kernel(Scor
 
     const int bi = hh / a.Hq, h = hh - bi * a.Hq;
     const int g = h / a.G, hg = h - g * a.G;
-    const int Tb = a.Tk - bi * kBlkRows, Wb = min(kBlkRows, Tb);
+    const int Tb = a.Tk - bi * kBlkRows, Wb = min(kBlkRows, a.q_rows - bi * kBlkRows);
     const int pos0 = Tb - Wb + hf * kBlkHalf;          // position of the half's first row
     const int rows = min(kBlkHalf, Wb - hf * kBlkHalf);  // rows the half really has (may be <= 0)
     const char* stage = smem + kTileBytes + (item & 1) * kStageBytes;
@@ -280,7 +284,7 @@ static hipError_t launch_blocks_t(const Plan& p, const ScoreArgs& a, hipStream_t
 
 // Rows of at most 256 bytes (two stages of 64 KB) and few enough kv heads for the column sums to fit beside them.
 bool score_accum_blocks_supported(const Plan& p) {
-  if (p.n_blocks <= 1 || p.R != p.T || p.d * p.elt > 256) return false;
+  if (!p.blocks || p.d * p.elt > 256) return false;
   const size_t lds = p.dtype == MEDA_BF16 ? (p.d == 128 ? blocks_lds_bytes<bf16_t, 128>(p.Hkv) : blocks_lds_bytes<bf16_t, 64>(p.Hkv))
                                           : blocks_lds_bytes<float, 64>(p.Hkv);
   return lds <= 160 * 1024;

@@ -226,7 +226,7 @@ static hipError_t launch_dma_t(const Plan& p, const ScoreArgs& a, hipStream_t s)
 // Grouped heads (one key tile buffer), windows of at most three 32-row blocks (four waves), rows of at most 256
 // bytes (two stages fit twice per CU).
 bool score_accum_dma_supported(const Plan& p) {
-  return p.n_blocks == 1 && p.accumulate == 0 && p.G >= 2 && p.RB <= 3 && p.d * p.elt <= 256;
+  return !p.blocks && p.accumulate == 0 && p.G >= 2 && p.RB <= 3 && p.d * p.elt <= 256;
 }
 
 hipError_t launch_score_accum_dma(const Plan& p, const Buffers& b, hipStream_t s) {

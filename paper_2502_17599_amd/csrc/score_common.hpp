@@ -39,21 +39,22 @@ struct ScoreArgs {
   int q_row0;      // first query row of this launch in the buffer
   int NTk;         // tiles per layer in ent_part
   int accumulate;  // add to col_scores / ent_part instead of storing
-  // Every prompt row scores (n_blocks > 1): the rows are cut into blocks of row_block rows counted from the end of
-  // the prompt; block bi holds the rows [Tb - Wb, Tb) with Tb = Tk - bi * row_block, Wb = min(row_block, Tb), and
-  // sees only the keys below Tb, so it is the window computation of the sequence cut at Tb.  The kernels derive
-  // T, W and q_row0 of their block themselves (one launch covers all blocks).
-  int n_blocks, row_block;
+  // Row-block mode (blocks; q_rows scoring rows, the last positions of the sequence): the rows are cut
+  // into blocks of row_block rows counted from the end; block bi holds the positions [Tb - Wb, Tb) with
+  // Tb = Tk - bi * row_block, Wb = min(row_block, q_rows - bi * row_block), and sees only the keys below Tb, so it is
+  // the window computation of the sequence cut at Tb.  The kernels derive T, W and q_row0 of their block themselves
+  // (one launch covers all blocks).
+  int blocks, row_block;
   int stats_rows;  // rows per (layer, head) in stats / stats_part (the padded window, or all Tk rows)
   int stats_row0;  // first row of this launch's (or block's) rows in them
   float c;             // scale * log2(e)
 };
 
-// The arguments of row block bi (see ScoreArgs::n_blocks).
+// The arguments of row block bi (see ScoreArgs::blocks).
 __device__ __forceinline__ void select_row_block(ScoreArgs& a, int bi) {
   a.T = a.Tk - bi * a.row_block;
-  a.W = min(a.row_block, a.T);
-  a.q_row0 = a.T - a.W;
+  a.W = min(a.row_block, a.q_rows - bi * a.row_block);  // the first rows may leave the last block short
+  a.q_row0 = a.q_rows - bi * a.row_block - a.W;
   a.stats_row0 = a.q_row0;
   a.accumulate = bi > 0;
 }
@@ -73,11 +74,11 @@ inline ScoreArgs make_args(const Plan& p, const Buffers& b, bool pass_a = false)
   a.L = p.L; a.Hq = p.Hq; a.Hkv = p.Hkv; a.G = p.G; a.T = p.Tb; a.W = p.Wb; a.RB = p.RB; a.Wp = p.Wp;
   a.Lseq = p.Lseq; a.Tk = p.Tk; a.q_rows = p.R; a.q_row0 = p.q_row0; a.NTk = p.NTk; a.accumulate = p.accumulate;
   a.NCG = p.NCG; a.CS = p.CS; a.CH = p.CH; a.NPART = p.NPART; a.NT = p.NT;
-  a.n_blocks = p.n_blocks; a.row_block = kScoreRowBlock;
-  a.stats_rows = p.n_blocks > 1 ? p.R : p.Wp; a.stats_row0 = 0;
+  a.blocks = p.blocks; a.row_block = kScoreRowBlock;
+  a.stats_rows = p.blocks ? p.R : p.Wp; a.stats_row0 = 0;
   if (pass_a) {  // pass A has its own row blocks when every prompt row scores
     a.RB = p.RBa;
-    if (p.n_blocks > 1) a.row_block = p.row_block_a;
+    if (p.blocks) a.row_block = p.row_block_a;
   }
   a.c = p.scale_log2;
   return a;

@@ -6,7 +6,7 @@
 namespace meda {
 
 // ------------------------------------------------------------------------------------------ pass A
-// grid (NCH, Hkv, L), or (NCH, Hkv * n_blocks, L) when every prompt row scores; NCG*CS waves.
+// grid (NCH, Hkv, L), or (1, Hkv * row blocks, L) in the row-block mode (more than 128 scoring rows); NCG*CS waves.
 // Wave (cg, cs) keeps NQ query fragments ((head of the group, row
 // block) pairs cg*NQ .. cg*NQ+NQ-1) in registers and visits the 32-key blocks sb = cs, cs+CS, ... of
 // every tile of its chunk.  The product is taken with the keys as operand A and the queries as
@@ -32,7 +32,7 @@ __global__ void __launch_bounds__(NW * 64, (NQ == 1 && NW == 4 && sizeof(T) == 2
 
   const int ch = blockIdx.x, l = blockIdx.z;
   int g = blockIdx.y, bi = 0;
-  if (BLOCKS) {  // every prompt row scores: this workgroup's row block (the largest blocks are dispatched first)
+  if (BLOCKS) {  // row-block mode: this workgroup's row block (the largest blocks are dispatched first)
     bi = blockIdx.y / a.Hkv;
     g = blockIdx.y - bi * a.Hkv;
     select_row_block(a, bi);
@@ -264,8 +264,8 @@ __global__ void __launch_bounds__(256) stats_combine_kernel(ScoreArgs a) {
   const int row = idx % a.stats_rows;
   const int n_part = a.NPART;
   int position;  // the row's position in the sequence
-  if (a.n_blocks > 1) {
-    position = row;  // one chunk of keys per row block: every partial of the row exists
+  if (a.blocks) {
+    position = a.Tk - a.q_rows + row;  // one chunk of keys per row block: every partial of the row exists
   } else {
     if (row >= a.W) {  // padding rows of the window: no weight
       float* plane = reinterpret_cast<float*>(a.stats) + (size_t)(idx / a.stats_rows) * 4 * a.stats_rows + row;
@@ -288,10 +288,10 @@ __global__ void __launch_bounds__(256) stats_combine_kernel(ScoreArgs a) {
   const bool row_is_vision = a.mask[(size_t)(l / a.Lseq) * a.Tk + position] != 0;
   const float coef_v = (!row_is_vision && zv > 0.f) ? 1.0f / zv : 0.f;  // text row: attends to vision columns
   const float coef_t = (row_is_vision && zt > 0.f) ? 1.0f / zt : 0.f;   // vision row: attends to text columns
-  if (a.n_blocks > 1) {
+  if (a.blocks) {
     // The statistics are stored as four planes of stats_rows values per (layer, head), so that pass B can copy the
-    // values of a row block and a plane as one contiguous piece.  Every prompt row scores: the planes hold the form
-    // the inner loop of that mode wants.  The probability of key j is
+    // values of a row block and a plane as one contiguous piece.  Row-block mode: the planes hold the form the inner
+    // loop of that mode wants.  The probability of key j is
     // exp2(c * (q.k_j + bias)) with bias = -(M + log2 Z) / c, which pass B puts into the accumulators before the
     // matrix products; the cross-modal probability is that times Z / Z_cross (0 for rows of the wrong modality or
     // without cross-modal mass).
@@ -333,10 +333,10 @@ static hipError_t launch_stats_w(const Plan& p, const ScoreArgs& a, hipStream_t 
   // read reaches, and three workgroups per CU of the small register-staged form do that best.
   constexpr bool kCanDma = Tile<T, D>::kRowBytes <= 256;
   if constexpr (kCanDma) {
-    if (p.n_blocks > 1) return launch_stats_b<T, D, NQ, NW, true, true>(p, a, s);
+    if (p.blocks) return launch_stats_b<T, D, NQ, NW, true, true>(p, a, s);
     if (p.G >= 2) return launch_stats_b<T, D, NQ, NW, false, true>(p, a, s);
   }
-  return p.n_blocks > 1 ? launch_stats_b<T, D, NQ, NW, true, false>(p, a, s) : launch_stats_b<T, D, NQ, NW, false, false>(p, a, s);
+  return p.blocks ? launch_stats_b<T, D, NQ, NW, true, false>(p, a, s) : launch_stats_b<T, D, NQ, NW, false, false>(p, a, s);
 }
 
 template <typename T, int D, int NQ>
@@ -361,7 +361,7 @@ hipError_t launch_score_stats(const Plan& p, const Buffers& b, hipStream_t s) {
 
 hipError_t launch_stats_combine(const Plan& p, const Buffers& b, hipStream_t s) {
   const ScoreArgs a = make_args(p, b);
-  const int total = p.L * p.Hq * (p.n_blocks > 1 ? p.R : p.Wp);
+  const int total = p.L * p.Hq * (p.blocks ? p.R : p.Wp);
   hipLaunchKernelGGL(stats_combine_kernel, dim3((total + 255) / 256), dim3(256), 0, s, a);
   return hipGetLastError();
 }

@@ -46,9 +46,12 @@ def test_workspace_bytes_valid_and_invalid(lib):
     assert pkg.meda_workspace_bytes(_params()) % 256 == 0
     for bad in (dict(n_layers=0), dict(n_q_heads=7), dict(head_dim=96), dict(window=0), dict(window=2000),
                 dict(total_budget=4 * 31), dict(total_budget=4 * 1000 + 1), dict(recent_den=0),
-                dict(recent_num=5, recent_den=4), dict(dtype=7), dict(window=129, seq_len=4096, total_budget=4 * 500),
+                dict(recent_num=5, recent_den=4), dict(dtype=7), dict(n_q_heads=66, n_kv_heads=2),
                 dict(n_layers=300, total_budget=300 * 250), dict(n_seqs=-1), dict(n_seqs=65)):
         assert pkg.meda_workspace_bytes(_params(**bad)) == 0, bad
+    # observation windows of more than 128 rows take the row-block mode of the scoring kernels
+    assert pkg.meda_workspace_bytes(_params(window=129, seq_len=4096, total_budget=4 * 500)) > 0
+    assert pkg.meda_workspace_bytes(_params(window=1000, total_budget=4 * 1000)) > 0
     # a batch: the workspace grows with the number of sequences (64 x 4 layers is the largest batch of this shape)
     one, four = pkg.meda_workspace_bytes(_params()), pkg.meda_workspace_bytes(_params(n_seqs=4))
     assert pkg.meda_workspace_bytes(_params(n_seqs=1)) == one and 3 * one < four <= 4 * one + 4096

@@ -146,6 +146,28 @@ def test_large_window_and_large_groups():
                   layout=layout, window=96, total_budget=2 * 260, seed=9))
 
 
+def test_windows_of_more_than_128_rows_take_the_row_block_mode():
+    # 200 rows (fp32, one query head per kv head: a 256-row block whose second half is short), 300 rows with grouped
+    # heads and vision rows inside the window (bf16: 96-row blocks of 32 in pass A, two 256-row blocks in pass B),
+    # and a window as long as the sequence
+    layout = (("t", 40, -1), ("v", 300, 0), ("t", 30, -1), ("v", 300, 1), ("t", 10, -1), ("v", 200, 2), ("t", 120, -1))
+    _case(variant(TINY, name="w200_f32", n_layers=2, n_q_heads=4, n_kv_heads=4, layout=layout, window=200,
+                  total_budget=2 * 320, seed=31))
+    _case(variant(TINY, name="w300_g4", n_layers=3, n_q_heads=8, n_kv_heads=2, head_dim=128, dtype="bf16",
+                  layout=layout, window=300, total_budget=3 * 420, seed=32))
+    short = (("v", 140, 0), ("t", 60, -1), ("v", 100, 1), ("t", 50, -1))
+    _case(variant(TINY, name="w350_eq_t", n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=64, dtype="bf16",
+                  layout=short, window=350, total_budget=2 * 350, seed=33))
+
+
+def test_sixteen_query_heads_per_kv_head_with_a_96_row_window():
+    # 48 (head, 32-row block) pairs per kv head: more than a workgroup of the window kernels holds, so the scoring
+    # runs in the row-block mode although the window has fewer than 128 rows
+    layout = (("t", 30, -1), ("v", 500, 0), ("t", 100, -1), ("v", 340, 1), ("t", 54, -1))
+    _case(variant(TINY, name="w96_g16", n_layers=2, n_q_heads=16, n_kv_heads=1, head_dim=128, dtype="bf16",
+                  layout=layout, window=96, total_budget=2 * 260, seed=34))
+
+
 def test_phase_timers_all_and_single():
     import paper_2502_17599_amd as pkg
     wl = variant(TINY, name="timers")
