@@ -8,10 +8,13 @@
 //   pass B  score_accum_kernel   recomputes the logits, adds normalised probabilities into the column
 //                                scores A_s and into the head-averaged cross-modal matrix, whose row
 //                                entropies are reduced per tile
+//           score_accum_dma_kernel     the same arithmetic for grouped heads, fed by asynchronous copies
+//           score_accum_blocks_kernel  the row-block mode (more than 128 scoring rows)
 // Logits are kept in the base-2 domain: t = (q.k) * scale * log2(e), probabilities are exp2(t - max).
-// This header holds what the two passes share: the argument block and its filling from the plan.  Each pass is a
-// translation unit of its own (score_stats.hip, score_accum.hip): both sit at the edge of their register budgets
-// and the compiler's allocation for one kernel shifted when the other lived in the same module.
+// This header holds what the passes share: the argument block and its filling from the plan.  Pass A and each form
+// of pass B are translation units of their own (score_stats.hip, score_accum.hip, score_accum_dma.hip,
+// score_accum_blocks.hip): they sit at the edge of their register budgets and the compiler's allocation for one
+// kernel shifted when another lived in the same module.
 #pragma once
 #include <type_traits>
 
@@ -20,14 +23,13 @@
 
 namespace meda {
 
-
 struct ScoreArgs {
   const char* q;
   const char* k;
   const uint8_t* mask;  // [N][Tk]: layer l belongs to sequence l / Lseq
-  float4* stats_part;  // [L][Hq][Wp][NPART] (max, Z_vision, Z_text, -)
+  float4* stats_part;  // [L][Hq][stats_rows][NPART] (max, Z_vision, Z_text, -)
   float4* stats;       // [L][Hq][4][stats_rows] floats: planes of (max, 1/Z_all, coef for vision columns, coef for text
-                       // columns), or of their full-prompt form (stats_combine_kernel)
+                       // columns), or of the form the row-block mode uses (stats_combine_kernel)
   float* inv_norm;     // [L][Hkv][T]
   float* col_scores;   // [L][Hkv][T]
   double* ent_part;    // [L][NT][2]
@@ -45,7 +47,7 @@ struct ScoreArgs {
   // the window computation of the sequence cut at Tb.  The kernels derive T, W and q_row0 of their block themselves
   // (one launch covers all blocks).
   int blocks, row_block;
-  int stats_rows;  // rows per (layer, head) in stats / stats_part (the padded window, or all Tk rows)
+  int stats_rows;  // rows per (layer, head) in stats / stats_part (the padded window, or all q_rows rows)
   int stats_row0;  // first row of this launch's (or block's) rows in them
   float c;             // scale * log2(e)
 };
