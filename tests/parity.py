@@ -245,3 +245,23 @@ def check_all(wl, data, gpu, heads=None, score_layers=None, verbose=True, thread
     if verbose:
         print(f"[parity {wl.name}] " + ", ".join(f"{k}={v}" for k, v in stats.items()), flush=True)
     return stats
+
+
+def decode_error(got, ref, vmax, bf16):
+    """Checks one decoding step against the oracle and returns max |got - ref| / vmax.
+
+    The kernel multiplies exactly, sums d and S_l terms in fp32 and rounds the result once to the storage type.  The
+    fp32 part stays below 1e-6 of vmax (the largest |v| of the layer: the output is a convex combination of value
+    rows).  The rounding to bf16 (8 significant bits, round to nearest) moves a value x by up to half an ulp,
+    2^(floor(log2 |x|) - 8): a bound per element, which a single figure relative to vmax cannot replace (2^-9 vmax is
+    exceeded by an output just above a power of two close to vmax, 2^-8 vmax is loose everywhere else).
+    """
+    got = np.asarray(got, dtype=np.float64); ref = np.asarray(ref, dtype=np.float64)
+    tol = np.full(ref.shape, 1e-6 * vmax)
+    if bf16:
+        a = np.maximum(np.abs(ref), 2.0 ** -126)
+        tol = tol + 2.0 ** (np.floor(np.log2(a)) - 8)
+    diff = np.abs(got - ref)
+    bad = diff > tol
+    assert not bad.any(), (int(bad.sum()), float((diff - tol).max()), float(diff.max() / vmax))
+    return float(diff.max() / vmax)

@@ -9,6 +9,8 @@ from oracle import decode_oracle, meda_oracle
 from workloads import generate, generate_batch, get_workload, variant
 from workloads.gen import to_float64
 
+from parity import decode_error
+
 pytestmark = pytest.mark.gpu
 
 
@@ -118,8 +120,7 @@ def test_batch_grouped_heads_bf16_and_decode():
     torch.cuda.synchronize()
     ref = decode_oracle.decode_step(to_float64(q), out.k_out.double().cpu().numpy(), out.v_out.double().cpu().numpy(),
                                     seq.layer_len.cpu().numpy(), seq.layer_off.cpu().numpy(), base.n_kv_heads)
-    err = np.abs(att.double().cpu().numpy() - ref).max() / np.abs(out.v_out.double().cpu().numpy()).max()
-    assert err <= 1e-6 + 2.0 ** -9, err
+    decode_error(att.double().cpu().numpy(), ref, np.abs(out.v_out.double().cpu().numpy()).max(), True)
 
 
 @pytest.mark.parametrize("cfg", [

@@ -13,6 +13,8 @@ from oracle import decode_oracle as D
 from workloads import generate, get_workload, variant
 from workloads.gen import to_float64
 
+from parity import decode_error
+
 pytestmark = pytest.mark.gpu
 
 
@@ -45,10 +47,8 @@ def _case(wl, n_new, seed):
     ref = D.decode_step(to_float64(q.cpu()), kc, vc, cache.layer_len.cpu().numpy(), cache.layer_off.cpu().numpy(),
                         wl.n_kv_heads, None if k_new is None else to_float64(k_new.cpu()),
                         None if v_new is None else to_float64(v_new.cpu()))
-    tol = 1e-6 + (2.0 ** -9 if dt == torch.bfloat16 else 0.0)
     vmax = max(np.abs(vc).max(), 0.0 if v_new is None else float(v_new.abs().max()))
-    err = float(np.abs(got.to(torch.float64).cpu().numpy() - ref).max() / vmax)
-    assert err <= tol, err
+    err = decode_error(got.to(torch.float64).cpu().numpy(), ref, vmax, dt == torch.bfloat16)
     print(f"[no-alloc case] bit-identical to the workspace entry point; error against the oracle {err:.2e}", flush=True)
 
 
