@@ -118,14 +118,15 @@ __device__ __forceinline__ void keep_if_improved(const f32x16_t& u, float bm, in
   }
 }
 
-// Slot of the row's best: the lowest register of the saved block that holds the maximum.
-// best - u[r] is +0 exactly there and positive elsewhere, and the bit patterns of non-negative floats
-// order like unsigned integers, so the minimum of (bits << 4 | r) carries r of the first maximum.
+// Slot of the row's best: the lowest register of the saved block that holds the maximum.  `best` is the maximum of
+// exactly these 16 values (the max3 tree of keep_if_improved's caller), so one of them compares equal to it; walking
+// down from register 15 leaves the lowest such register.  (Not a search for the smallest best - u[r] through a packed
+// integer key: a key of 32 bits has no room for all 31 bits of a non-negative float beside the 4 bits of r, and
+// whichever float bits are dropped, some nonzero difference then packs to the same key as the zero of the maximum.)
 __device__ __forceinline__ int row_best_slot(const RowBest& rb, int kg) {
-  unsigned key = 0xffffffffu;
+  int ridx = 15;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) key = min(key, (__float_as_uint(rb.best - rb.u[r]) << 4) | (unsigned)r);
-  const int ridx = (int)(key & 15u);
+  for (int r = 14; r >= 0; --r) ridx = (rb.u[r] == rb.best) ? r : ridx;
   return rb.slot0 + (ridx >> 2) * 8 + kg * 4 + (ridx & 3);
 }
 

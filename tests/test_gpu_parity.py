@@ -168,6 +168,41 @@ def test_sixteen_query_heads_per_kv_head_with_a_96_row_window():
                   layout=layout, window=96, total_budget=2 * 260, seed=34))
 
 
+def test_argmax_when_another_slot_of_the_block_trails_the_best_by_exactly_two():
+    """Crafted keys for the search of the winning slot inside a block of 32 (Section 3.3, merging: each key that is
+    not conserved goes to the conserved key it is most similar to).  The conserved keys are unit vectors along the
+    axes, so the scaled product of a row with slot s is the row's component s, exactly.  Row 0 has 1 on axis 0 and 3
+    on axis 1: its best slot is 1, and slot 0, which sits in a lower register of the same lane, trails it by exactly
+    2.0, a float whose low 28 bits are zero.  (A search that packs the difference and the register into one 32-bit
+    key and drops high bits of the float sends this row to slot 0.)  The other rows probe differences of 0.5, 2^-31,
+    8 and an exact tie."""
+    T, S, d = 96, 32, 64
+    layout = (("v", 32, 0), ("t", 64, -1))
+    wl = variant(TINY, name="argmax_exact_two", n_layers=1, n_q_heads=1, n_kv_heads=1, head_dim=d, dtype="f32",
+                 layout=layout, window=1, total_budget=S, recent_num=1, recent_den=1, seed=41)
+    print(f"\n[case] {wl.name}: crafted keys, T={T} S={S}", flush=True)
+    data = generate(wl)
+    k = torch.zeros(1, 1, T, d, dtype=torch.float32)
+    g = torch.Generator().manual_seed(3)
+    k[0, 0, :T - S] = 0.01 * torch.randn(T - S, d, generator=g)
+    for s_ in range(S):                         # the recent part (all of the budget): one axis each
+        k[0, 0, T - S + s_, s_] = 1.0
+    rows = {0: {0: 1.0, 1: 3.0}, 1: {4: 2.5, 9: 3.0}, 2: {2: 1.0, 3: 1.0 + 2.0 ** -31, 7: 1.0},
+            3: {8: 1.0, 21: 9.0}, 4: {5: 2.0, 6: 2.0, 30: 2.0}, 5: {31: 4.0, 15: 2.0}, 6: {16: 3.0, 0: 1.0}}
+    for r_, comps in rows.items():
+        k[0, 0, r_] = 0.0
+        for axis, val in comps.items():
+            k[0, 0, r_, axis] = val
+    data = dict(data, k=k)
+    comp, gpu = run_gpu(wl, data)
+    assert list(gpu["sel_idx"][:S]) == list(range(T - S, T))      # the conserved keys are the last S positions
+    ma = gpu["merge_assign"][0, 0]
+    want = {0: 1, 1: 9, 2: 2, 3: 21, 4: 5, 5: 31, 6: 16}           # ties (rows 2 and 4) go to the lowest slot
+    got = {r_: int(ma[r_]) for r_ in want}
+    assert got == want, got
+    check_all(wl, data, gpu)
+
+
 def test_phase_timers_all_and_single():
     import paper_2502_17599_amd as pkg
     wl = variant(TINY, name="timers")
