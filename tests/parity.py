@@ -150,7 +150,12 @@ def check_head(wl, data, gpu, a_s_oracle, l, g, n_top, n_recent, stats):
         kth = np.sort(cand)[::-1][n_top - 1]
         diff = np.setxor1d(idx_gpu, idx_c)
         assert len(idx_gpu) == len(idx_c) and np.all(np.diff(idx_gpu) > 0), "conserved set malformed"
-        assert np.all(np.abs(boosted[diff] - kth) <= 1e-4 * abs(kth)), \
+        # The selection is decided in the kernel's precision, fp32: a probability below the smallest normal number
+        # (2^-126) may reach the column sum as zero, so scores that differ by less than (terms summed) x 2^-126
+        # cannot be told apart there, however far apart they are in the oracle's fp64 (a single window row with a
+        # sharp softmax leaves most columns below 1e-40).
+        floor = wl.n_score_rows * (wl.n_q_heads // wl.n_kv_heads) * 2.0 ** -126
+        assert np.all(np.abs(boosted[diff] - kth) <= 1e-4 * abs(kth) + floor), \
             f"layer {l} head {g}: index sets differ outside the 1e-4 tie band at {diff[:8]}"
         stats["sets_differing_in_tie_band"] += 1
         idx_c = idx_gpu.astype(np.int64)

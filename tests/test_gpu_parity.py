@@ -203,6 +203,17 @@ def test_argmax_when_another_slot_of_the_block_trails_the_best_by_exactly_two():
     check_all(wl, data, gpu)
 
 
+def test_single_window_row_with_scores_below_the_fp32_range():
+    # one query row, a sharp softmax and a budget of three quarters of the sequence: the heavy keys take all the
+    # probability and most columns have a score below 1e-40, which fp32 cannot rank; the conserved sets may differ
+    # from the fp64 oracle's only inside that band (parity.py), everything downstream is checked on the GPU's set
+    layout = (("t", 20, -1), ("v", 300, 0), ("t", 30, -1), ("v", 300, 1), ("t", 127, -1))
+    stats = _case(variant(TINY, name="w1_sharp", n_layers=2, n_q_heads=2, n_kv_heads=2, head_dim=128, dtype="bf16",
+                          layout=layout, window=1, total_budget=2 * 580, recent_num=1, recent_den=2, seed=26004,
+                          tau_lo=2.5, tau_hi=3.0, heavy_frac=0.02))
+    print("  conserved sets that differ inside the tie band:", stats["sets_differing_in_tie_band"])
+
+
 def test_phase_timers_all_and_single():
     import paper_2502_17599_amd as pkg
     wl = variant(TINY, name="timers")
