@@ -358,6 +358,209 @@ __global__ void __launch_bounds__(kDecThreads, 2) decode_partial_kernel(DecodeAr
   }
 }
 
+// The same partial step on the matrix unit, for bf16 rows of 128 elements and groups of 5 to 8 query heads, where
+// the kernel above is bound by the vector ALU (about 160 vector instructions per 32 bytes a lane reads) and not by
+// HBM.  A wave takes 16 rows per step:
+//   logits  D[key][head] = sum_d K[key][d] Q[head][d]    4 x v_mfma_f32_16x16x32_bf16 (exact products, fp32 sums)
+//   output  O[head][col] += sum_key P[key][head] V[key][col]   32 x v_mfma_f32_16x16x4_f32 (fp32 weights and values)
+// Lane l = (c, g) = (l % 16, l / 16).  For the logits it holds the pieces g, 4+g, 8+g, 12+g (16 bytes each) of key c
+// and of query head c, and receives the logits of head c for the keys 4g .. 4g+3.  The second product runs over the
+// keys in four instructions i = 0..3, instruction i taking the keys {4g' + i} with g' as its k index: its weight
+// operand is then this lane's own register i (no cross-lane movement), and its value operand element j of piece c of
+// key 4g + i, which the lane loads itself.  Output column 8c + j of the heads 4g .. 4g+3 accumulates in this lane.
+// The running maximum of a head is kept common to the four lane groups (they hold different keys of the same
+// head); the normaliser is summed per group and merged at the end.
+constexpr int kDecMfmaRows = 16;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+// FP8: the cached rows are E4M3 codes with one scale per row (pieces of 8 bytes; keys become packed bf16 on arrival,
+// which is exact, and the key's scale multiplies the logit; values become fp32 and their scale rides on the weight);
+// the launch then covers the cached rows only.
+template <int D, bool FP8>
+__global__ void __launch_bounds__(kDecThreads, 2) decode_partial_mfma_kernel(DecodeArgs a) {
+  static_assert(D == 128, "16 pieces per row: one per lane of a lane group");
+  constexpr int kRowBytes = D * 2;                     // bf16 rows (queries, appended rows, the bf16 cache)
+  constexpr int kCacheRowBytes = FP8 ? D : kRowBytes;  // rows of the cache this launch reads
+  constexpr int kPiece = FP8 ? 8 : 16;
+  constexpr int GPM = 16;  // heads the matrix shapes hold (a.G <= 8 of them are real)
+  __shared__ float red_o[kDecWaves][8][D];
+  __shared__ float red_m[kDecWaves][8], red_z[kDecWaves][8];
+
+  const int sp = blockIdx.x + a.sp0, g = blockIdx.y, l = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int c = lane & 15, grp = lane >> 4;
+
+  const char *kb, *vb;
+  const float *ksc = nullptr, *vsc = nullptr;
+  int r_beg, r_end;
+  if (FP8 || sp < a.NS) {
+    const int S = a.layer_len[l];
+    const int chunk = (S + a.NS - 1) / a.NS;
+    r_beg = sp * chunk;
+    r_end = min(S, r_beg + chunk);
+    const size_t row0 = (size_t)a.layer_off[l] * a.Hkv + (size_t)g * S;
+    kb = a.k_cache + row0 * kCacheRowBytes;
+    vb = a.v_cache + row0 * kCacheRowBytes;
+    if (FP8) {
+      ksc = a.k_scale + row0;
+      vsc = a.v_scale + row0;
+    }
+  } else {
+    const int chunk = (a.n_new + a.NSN - 1) / a.NSN;
+    r_beg = (sp - a.NS) * chunk;
+    r_end = min(a.n_new, r_beg + chunk);
+    const size_t base = ((size_t)(l * a.Hkv + g) * a.n_new) * kRowBytes;
+    kb = a.k_new + base;
+    vb = a.v_new + base;
+  }
+
+  // query head c of the group (heads past G: zeros, their columns are dropped)
+  uint4 qp[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    qp[ks] = make_uint4(0u, 0u, 0u, 0u);
+    if (c < a.G) qp[ks] = *reinterpret_cast<const uint4*>(a.q + (size_t)(l * a.Hq + g * a.G + c) * kRowBytes + (4 * ks + grp) * 16);
+  }
+
+  float m_run = kNegBig, z_run = 0.f;  // of head c; m_run is the same in the four lane groups
+  f32x4_t acc[8];                      // acc[j][r]: output column 8c + j of head 4 grp + r
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  // a step's loads: four key pieces (packed bf16 after the load), four value pieces (codes stay codes until they
+  // are needed as floats), and with FP8 the scales of the keys 4 grp + i this lane has logits and weights for
+  auto load_step = [&](int r0, uint4 (&kv)[4], uint4 (&vv)[4], float (&sk)[4], float (&sv)[4]) {
+    const int rk = min(r0 + c, r_end - 1);  // rows past the end repeat the last one (their weights are zero)
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const char* src = kb + (size_t)rk * kCacheRowBytes + (4 * ks + grp) * kPiece;
+      if constexpr (FP8) kv[ks] = e4m3x8_to_bf16x8(load8_stream(src)); else kv[ks] = load16_stream(src);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int rv = min(r0 + 4 * grp + i, r_end - 1);
+      const char* src = vb + (size_t)rv * kCacheRowBytes + c * kPiece;
+      if constexpr (FP8) {
+        const uint2 vc = load8_stream(src);
+        vv[i] = make_uint4(vc.x, vc.y, 0u, 0u);
+        sk[i] = ksc[rv];
+        sv[i] = vsc[rv];
+      } else {
+        vv[i] = load16_stream(src);
+        sk[i] = sv[i] = 1.0f;
+      }
+    }
+  };
+
+  constexpr int kStepStride = kDecWaves * kDecMfmaRows;
+  int r0 = r_beg + wave * kDecMfmaRows;
+  uint4 kv[4], vv[4];
+  float sk[4], sv[4];
+  if (r0 < r_end) load_step(r0, kv, vv, sk, sv);
+  for (; r0 < r_end; r0 += kStepStride) {
+    uint4 kn[4], vn[4];
+    float skn[4], svn[4];
+    const bool more = r0 + kStepStride < r_end;
+    if (more) load_step(r0 + kStepStride, kn, vn, skn, svn);  // in flight while this step is computed
+
+    f32x4_t s4 = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+      s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kv[ks]), __builtin_bit_cast(bf16x8_t, qp[ks]),
+                                                   s4, 0, 0, 0);
+    // this lane: head c, keys r0 + 4 grp + i
+    float t[4];
+    float bm = kNegBig;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      t[i] = (r0 + 4 * grp + i < r_end) ? (FP8 ? s4[i] * sk[i] * a.scale_log2 : s4[i] * a.scale_log2) : kNegBig;
+      bm = fmaxf(bm, t[i]);
+    }
+    bm = fmaxf(bm, __shfl_xor(bm, 16, kWave));
+    bm = fmaxf(bm, __shfl_xor(bm, 32, kWave));
+    if (__ballot(bm > m_run) != 0ull) {  // a new maximum of some head: rescale what that head has so far (rare)
+      const float mn = fmaxf(m_run, bm);
+      const float c1 = __builtin_amdgcn_exp2f(m_run - mn);
+      z_run *= c1;
+      m_run = mn;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float cr = __shfl(c1, 4 * grp + r, kWave);  // the factor of head 4 grp + r (lane 4 grp + r of group 0)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j][r] *= cr;
+      }
+    }
+    float p[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      p[i] = (r0 + 4 * grp + i < r_end) ? __builtin_amdgcn_exp2f(t[i] - m_run) : 0.f;
+      z_run += p[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float vf[8];
+      if constexpr (FP8) {
+        e4m3x2_to_float(vv[i].x, false, vf[0], vf[1]);
+        e4m3x2_to_float(vv[i].x, true, vf[2], vf[3]);
+        e4m3x2_to_float(vv[i].y, false, vf[4], vf[5]);
+        e4m3x2_to_float(vv[i].y, true, vf[6], vf[7]);
+      } else {
+        Elems<bf16_t>::unpack(vv[i], vf);
+      }
+      const float w = FP8 ? p[i] * sv[i] : p[i];  // the value row's scale rides on its weight
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(w, vf[j], acc[j], 0, 0, 0);
+    }
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        kv[i] = kn[i];
+        vv[i] = vn[i];
+        sk[i] = skn[i];
+        sv[i] = svn[i];
+      }
+    }
+  }
+  // the four lane groups saw different keys of head c: one normaliser
+  z_run += __shfl_xor(z_run, 16, kWave);
+  z_run += __shfl_xor(z_run, 32, kWave);
+
+  // merge the waves through LDS (as in the kernel above)
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int h = 4 * grp + r;
+    if (h < 8) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) red_o[wave][h][8 * c + j] = acc[j][r];
+    }
+  }
+  if (grp == 0 && c < 8) {
+    red_m[wave][c] = m_run;
+    red_z[wave][c] = z_run;
+  }
+  __syncthreads();
+  for (int i = tid; i < a.G * D; i += kDecThreads) {
+    const int h = i / D, j = i - h * D;
+    float mn = red_m[0][h];
+#pragma unroll
+    for (int w = 1; w < kDecWaves; ++w) mn = fmaxf(mn, red_m[w][h]);
+    float zs = 0.f, os = 0.f;
+#pragma unroll
+    for (int w = 0; w < kDecWaves; ++w) {
+      const float cw = __builtin_amdgcn_exp2f(red_m[w][h] - mn);
+      zs = fmaf(red_z[w][h], cw, zs);
+      os = fmaf(red_o[w][h][j], cw, os);
+    }
+    float* dst = a.part + ((size_t)(l * a.Hq + g * a.G + h) * a.NP + sp) * (D + 2);
+    dst[j] = os;
+    if (j == 0) {
+      dst[D] = mn;
+      dst[D + 1] = zs;
+    }
+  }
+}
+
 // grid (Hq, L), D threads: merges the NP chunks of one query head and writes the output row.
 template <typename T, int D>
 __global__ void __launch_bounds__(D) decode_combine_kernel(DecodeArgs a) {
@@ -414,13 +617,20 @@ static hipError_t launch_decode_g(const DecodePlan& pl, const DecodeArgs& a_in, 
   hipError_t e;
   if constexpr (sizeof(T) == 2) {
     if (a.k_scale) {  // 8-bit cache: its rows first, then the appended bf16 rows with the plain kernel
+      constexpr bool kMfma = D == 128 && GP == 8;  // groups of 5 to 8 heads: the matrix form (see its comment)
       a.sp0 = 0;
-      hipLaunchKernelGGL((decode_partial_kernel<T, D, GP, true>), dim3(pl.NS, pl.Hkv, pl.L), dim3(kDecThreads), 0, s, a);
+      if constexpr (kMfma)
+        hipLaunchKernelGGL((decode_partial_mfma_kernel<D, true>), dim3(pl.NS, pl.Hkv, pl.L), dim3(kDecThreads), 0, s, a);
+      else
+        hipLaunchKernelGGL((decode_partial_kernel<T, D, GP, true>), dim3(pl.NS, pl.Hkv, pl.L), dim3(kDecThreads), 0, s, a);
       e = hipGetLastError();
       if (e != hipSuccess) return e;
       if (pl.NSN > 0) {
         a.sp0 = pl.NS;
-        hipLaunchKernelGGL((decode_partial_kernel<T, D, GP, false>), dim3(pl.NSN, pl.Hkv, pl.L), dim3(kDecThreads), 0, s, a);
+        if constexpr (kMfma)
+          hipLaunchKernelGGL((decode_partial_mfma_kernel<D, false>), dim3(pl.NSN, pl.Hkv, pl.L), dim3(kDecThreads), 0, s, a);
+        else
+          hipLaunchKernelGGL((decode_partial_kernel<T, D, GP, false>), dim3(pl.NSN, pl.Hkv, pl.L), dim3(kDecThreads), 0, s, a);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
       }
@@ -429,7 +639,12 @@ static hipError_t launch_decode_g(const DecodePlan& pl, const DecodeArgs& a_in, 
     }
   }
   a.sp0 = 0;
-  hipLaunchKernelGGL((decode_partial_kernel<T, D, GP, false>), dim3(pl.NP, pl.Hkv, pl.L), dim3(kDecThreads), 0, s, a);
+  if constexpr (sizeof(T) == 2 && D == 128 && GP == 8) {
+    // groups of 5 to 8 heads: the vector form is bound by its instruction count, the matrix form by HBM
+    hipLaunchKernelGGL((decode_partial_mfma_kernel<D, false>), dim3(pl.NP, pl.Hkv, pl.L), dim3(kDecThreads), 0, s, a);
+  } else {
+    hipLaunchKernelGGL((decode_partial_kernel<T, D, GP, false>), dim3(pl.NP, pl.Hkv, pl.L), dim3(kDecThreads), 0, s, a);
+  }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(pl.Hq, pl.L), dim3(D), 0, s, a);
