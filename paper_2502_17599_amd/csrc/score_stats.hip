@@ -227,7 +227,10 @@ __global__ void __launch_bounds__(NW * 64, (NQ == 1 && NW == 4 && sizeof(T) == 2
             m[q] = mn;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-              const float e = (t[r] > 0.5f * kNegBig) ? fast_exp2(t[r] - mn) : 0.f;
+              // the exponent in the form pass B uses (one rounding, as in the plain path above): the probability of
+              // a row's largest logit is then the same number in both passes, and a nearly one-hot row keeps its
+              // normaliser consistent with its probabilities
+              const float e = (t[r] > 0.5f * kNegBig) ? fast_exp2(fmaf(acc[r], a.c, -mn)) : 0.f;
               const bool vis = (mword >> acc_row(r, kg)) & 1u;
               zv[q] += vis ? e : 0.f;
               zt[q] += vis ? 0.f : e;
