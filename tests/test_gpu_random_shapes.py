@@ -1,5 +1,6 @@
 """Seeded sweep over small shapes (sequence length, window, group size, head dimension, storage type, layout,
-budget, recent share) through the whole pass and one decoding step, against the oracles."""
+budget, recent share, scoring with the window or with every prompt row) through the whole pass and one decoding
+step, against the oracles."""
 import numpy as np
 import pytest
 
@@ -63,6 +64,23 @@ def _configs():
         out.append(variant(TINY, name=f"rand{i}", n_layers=L, n_q_heads=hkv * G, n_kv_heads=hkv, head_dim=d, dtype=dtype,
                            layout=_random_layout(r, T), window=W, total_budget=B, seed=100 + i, recent_num=num,
                            recent_den=den, tau_lo=0.3, tau_hi=3.0, heavy_frac=float(r.choice([0.0, 0.02, 0.1]))))
+    # a third draw for the row-block mode of the scoring kernels: windows of more than 128 rows, up to 32 query heads
+    # per kv head, and every prompt row scoring (three cases in ten)
+    r = np.random.Generator(np.random.Philox(key=[2024, 7]))
+    for i in range(40, 64):
+        T = int(r.choice([64, 129, 200, 256, 300, 513, 777, 1024, 1500, 2049]))
+        W = int(min(T, r.choice([16, 32, 64, 96, 128, 129, 150, 200, 256, 257, 300, 400, 512, 640])))
+        hkv = int(r.choice([1, 2, 3]))
+        G = int(r.choice([1, 2, 3, 4, 7, 8, 12, 16, 32]))
+        d = int(r.choice([64, 128]))
+        dtype = str(r.choice(["f32", "bf16"]))
+        L = int(r.integers(1, 3))
+        lo, hi = L * W, L * T
+        B = int(r.integers(lo, hi + 1)) if r.random() < 0.85 else int(r.choice([lo, hi]))
+        kw = dict(score_rows=T) if r.random() < 0.3 else {}
+        out.append(variant(TINY, name=f"rand{i}", n_layers=L, n_q_heads=hkv * G, n_kv_heads=hkv, head_dim=d, dtype=dtype,
+                           layout=_random_layout(r, T), window=W, total_budget=B, seed=100 + i, tau_lo=0.3, tau_hi=3.0,
+                           heavy_frac=float(r.choice([0.0, 0.02, 0.1])), **kw))
     return out
 
 
@@ -73,6 +91,8 @@ def test_random_shape(wl):
     data = generate(wl)
     comp, gpu = run_gpu(wl, data)
     check_all(wl, data, gpu)
-    # one decoding step over the cache this shape produces, with a few appended rows
-    from test_gpu_decode import _check as check_decode
-    check_decode(wl, n_new=wl.seed % 4)
+    # one decoding step over the cache this shape produces, with a few appended rows (the step takes up to 8 query
+    # heads per kv head and has no notion of scoring rows)
+    if wl.n_q_heads // wl.n_kv_heads <= 8 and wl.n_score_rows == wl.window:
+        from test_gpu_decode import _check as check_decode
+        check_decode(wl, n_new=wl.seed % 4)
