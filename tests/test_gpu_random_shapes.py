@@ -1,6 +1,6 @@
 """Seeded sweep over small shapes (sequence length, window, group size, head dimension, storage type, layout,
 budget, recent share, scoring with the window or with every prompt row) through the whole pass and one decoding
-step, against the oracles."""
+step, against the oracles; a second sweep runs such shapes with the ablation flags."""
 import numpy as np
 import pytest
 
@@ -96,3 +96,70 @@ def test_random_shape(wl):
     if wl.n_q_heads // wl.n_kv_heads <= 8 and wl.n_score_rows == wl.window:
         from test_gpu_decode import _check as check_decode
         check_decode(wl, n_new=wl.seed % 4)
+
+
+def _flag_configs():
+    """Shapes of both scoring modes, each with one of the three flag combinations."""
+    r = np.random.Generator(np.random.Philox(key=[2024, 8]))
+    out = []
+    for i in range(18):
+        T = int(r.choice([40, 64, 129, 200, 300, 513, 777, 1024, 1500]))
+        W = int(min(T, r.choice([1, 7, 32, 33, 64, 96, 128, 129, 200, 300])))
+        hkv = int(r.choice([1, 2, 3]))
+        G = int(r.choice([1, 2, 3, 4, 8, 16]))
+        d = int(r.choice([64, 128]))
+        dtype = str(r.choice(["f32", "bf16"]))
+        L = int(r.integers(1, 5))
+        lo, hi = L * W, L * T
+        B = int(r.integers(lo, hi + 1)) if r.random() < 0.85 else int(r.choice([lo, hi]))
+        num, den = [(3, 4), (0, 1), (1, 1), (1, 2)][int(r.integers(0, 4))]
+        kw = dict(score_rows=T) if r.random() < 0.25 else {}
+        wl = variant(TINY, name=f"flags{i}", n_layers=L, n_q_heads=hkv * G, n_kv_heads=hkv, head_dim=d, dtype=dtype,
+                     layout=_random_layout(r, T), window=W, total_budget=B, seed=300 + i, recent_num=num, recent_den=den,
+                     tau_lo=0.3, tau_hi=3.0, heavy_frac=float(r.choice([0.0, 0.02, 0.1])), **kw)
+        out.append((wl, 1 + i % 3))
+    return out
+
+
+@pytest.mark.parametrize("wl,flags", _flag_configs(), ids=lambda x: x.name if hasattr(x, "name") else f"flags={x}")
+def test_random_shape_with_flags(wl, flags):
+    """Uniform budgets (1): the layer lengths are B/L whatever the entropies are, and everything downstream matches the
+    oracle run with them.  No merge (2): the same conserved sets as the plain run, their rows copied bit for bit.
+    Both (3): the conserved sets of the uniform-budget run, copied."""
+    import paper_2502_17599_amd as pkg
+    from oracle import meda_oracle as O
+    from parity import check_head, gpu_head, oracle_scores
+    from workloads.gen import to_float64
+    assert (pkg.FLAG_UNIFORM_BUDGET, pkg.FLAG_NO_MERGE) == (1, 2)
+    print(f"\n[flag case] {wl.name} flags={flags}: L={wl.n_layers} Hq={wl.n_q_heads} Hkv={wl.n_kv_heads} d={wl.head_dim} "
+          f"T={wl.seq_len} W={wl.window} rows={wl.n_score_rows} B={wl.total_budget} {wl.dtype} "
+          f"recent={wl.recent_num}/{wl.recent_den}", flush=True)
+    data = generate(wl)
+    _, gpu = run_gpu(wl, data, flags=flags)
+    L, Hkv, T = wl.n_layers, wl.n_kv_heads, wl.seq_len
+    assert int(gpu["S"].sum()) == wl.total_budget and np.array_equal(np.diff(gpu["off"]), gpu["S"])
+    if flags & pkg.FLAG_UNIFORM_BUDGET:
+        S, M, N, off = O.allocate_budgets(np.zeros(L), wl.total_budget, T, wl.window, wl.recent_num, wl.recent_den)
+        assert gpu["S"].tolist() == S.tolist() and max(S) - min(S) <= 1 and list(S) == sorted(S, reverse=True)
+        assert np.array_equal(gpu["alloc"][:, 1], M) and np.array_equal(gpu["alloc"][:, 2], N)
+    if flags == pkg.FLAG_UNIFORM_BUDGET:
+        a_s, _ = oracle_scores(wl, data)
+        stats = {"heads": 0, "rows": 0, "ambiguous_rows": 0, "sets_differing_in_tie_band": 0,
+                 "max_kv_err": 0.0, "kv_elems_not_bit_exact": 0}
+        for l in range(L):
+            for g in range(Hkv):
+                check_head(wl, data, gpu, a_s[l], l, g, int(N[l]), int(M[l]), stats)
+        print(f"[flag case] {stats}", flush=True)
+        return
+    # no merge: the sets of the run that merges (same budget rule), the rows as stored
+    _, ref = run_gpu(wl, data, flags=flags & ~pkg.FLAG_NO_MERGE)
+    assert np.array_equal(gpu["S"], ref["S"]) and np.array_equal(gpu["sel_idx"], ref["sel_idx"])
+    assert np.array_equal(gpu["entropy"], ref["entropy"]) and np.array_equal(gpu["col_scores"], ref["col_scores"])
+    for l in range(L):
+        for g in range(Hkv):
+            idx, k_out, v_out = gpu_head(wl, gpu, l, g)
+            assert np.array_equal(k_out, to_float64(data["k"][l, g])[idx]), f"layer {l} head {g}: keys not copied"
+            assert np.array_equal(v_out, to_float64(data["v"][l, g])[idx]), f"layer {l} head {g}: values not copied"
+            ma = gpu["merge_assign"][l, g]
+            assert np.array_equal(ma[idx], np.arange(len(idx)))
+            assert np.all(ma[np.setdiff1d(np.arange(T), idx)] == -1)
