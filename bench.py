@@ -125,8 +125,10 @@ def time_pass(pkg, torch, wl, dev, steps, warmup, flags=0, n_seqs=0, phase_event
         roofline = {"kernel": dom, "launches": phase_kernels[dom], "bound": bound, "achieved": achieved,
                     "peak": peak, "unit": unit, "frac": achieved / peak,
                     # HBM bytes per launch are not measured by this program: the counter runs are separate
-                    # rocprofv3 runs whose summaries are kept under profiles/
-                    "traffic": None, "traffic_source": f"profiles/hbm_counters_{wl.name}.md (rocprofv3 --pmc runs)",
+                    # rocprofv3 runs; the figure is read from their committed summary (null if there is none)
+                    "traffic": None if full_prompt or seqs > 1 else counted_traffic(wl.name, dom),
+                    "traffic_unit": "bytes (fetch + write, scaled by the copy calibration)",
+                    "traffic_source": f"profiles/hbm_counters_{wl.name}.md (rocprofv3 --pmc runs)",
                     "work_per_launch": work[dom], "work_unit": "flop" if bound == "mfma" else "bytes",
                     "kernel_ms": dom_ms, "launches_timed": n_calls}
 
@@ -148,6 +150,21 @@ def time_pass(pkg, torch, wl, dev, steps, warmup, flags=0, n_seqs=0, phase_event
     }
     kept = (q, k, v, out, budgets[0]) if keep else None
     return rec, kept
+
+
+def counted_traffic(workload, phase):
+    """HBM bytes per launch of one phase (fetched + written) from the summary of the rocprofv3 counter runs of this
+    workload under profiles/, or None if that summary or the phase's row is missing."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"hbm_counters_{workload}.md")
+    try:
+        with open(path) as f:
+            for line in f:
+                cells = [c.strip() for c in line.strip().strip("|").split("|")]
+                if len(cells) == 4 and cells[0] == phase:
+                    return float(cells[3])
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def decode_step_record(pkg, torch, wl, out, q_dtype, k, v, dev, iters=50):

@@ -56,7 +56,8 @@ typedef struct {
   int32_t n_q_heads;    /* Hq                                                                      */
   int32_t n_kv_heads;   /* Hkv, Hq % Hkv == 0; query head h reads kv head h / (Hq/Hkv)             */
   int32_t head_dim;     /* d: 64 or 128                                                            */
-  int32_t seq_len;      /* T: cached positions per layer                                           */
+  int32_t seq_len;      /* T: cached positions per layer; T*d*sizeof(element) < 2^31, N*L*Hkv*T < 2^31
+                           and N*L*Hq*max(128, scoring rows) < 2^31 (MEDA_ERR_UNSUPPORTED beyond)      */
   int32_t window;       /* W: rows of q_win = the last W positions, 1 <= W <= T                      */
   int64_t total_budget; /* B = sum_l S_l, kept positions per kv head summed over layers            */
   int32_t recent_num;   /* M_l = max(min(W,S_l), floor(S_l*num/den)); 3/4 is the paper's 3:1 split */

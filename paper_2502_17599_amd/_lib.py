@@ -267,6 +267,33 @@ def meda_decode_workspace_bytes(params: MedaDecodeParams) -> int:
     return int(load_library().meda_decode_workspace_bytes(ctypes.byref(params)))
 
 
+def _check_decode_tensors(p: MedaDecodeParams, q, k_rows, v_rows, row_dtype, layer_len, layer_off, k_new, v_new,
+                          out=None) -> None:
+    """Shapes, types and placement of the tensors of one decoding step (the library sees only pointers)."""
+    dt = torch.bfloat16 if p.dtype == 1 else torch.float32
+    dev = q.device
+    def want(name, t, shape, dtype, exact=True):
+        ok = (t is not None and t.dtype == dtype and t.device == dev and t.is_contiguous() and t.dim() == len(shape)
+              and tuple(t.shape[1:]) == tuple(shape[1:])
+              and (t.shape[0] == shape[0] if exact else t.shape[0] >= shape[0]))
+        if not ok:
+            raise ValueError(f"{name}: expected a contiguous {dtype} tensor of shape {tuple(shape)}"
+                             f"{'' if exact else ' (or more rows)'} on {dev}")
+    if not q.is_cuda:
+        raise ValueError("q: expected a tensor on the GPU")
+    want("q", q, (p.n_layers, p.n_q_heads, p.head_dim), dt)
+    rows = p.total_budget * p.n_kv_heads
+    want("k cache", k_rows, (rows, p.head_dim), row_dtype, exact=False)
+    want("v cache", v_rows, (rows, p.head_dim), row_dtype, exact=False)
+    want("layer_len", layer_len, (p.n_layers,), torch.int32)
+    want("layer_off", layer_off, (p.n_layers + 1,), torch.int64)
+    if p.n_new > 0:
+        want("k_new", k_new, (p.n_layers, p.n_kv_heads, p.n_new, p.head_dim), dt)
+        want("v_new", v_new, (p.n_layers, p.n_kv_heads, p.n_new, p.head_dim), dt)
+    if out is not None:
+        want("out", out, (p.n_layers, p.n_q_heads, p.head_dim), dt)
+
+
 class Decoder:
     """Holds the workspace and the output row for meda_decode_attention calls with fixed parameters."""
 
@@ -282,6 +309,11 @@ class Decoder:
 
     def fp8(self, q, k_codes, v_codes, k_scales, v_scales, layer_len, layer_off, k_new=None, v_new=None, stream=None):
         """The step over a cache stored with meda_quantize_fp8 (bf16 queries only)."""
+        _check_decode_tensors(self.params, q, k_codes, v_codes, torch.uint8, layer_len, layer_off, k_new, v_new)
+        for name, t in (("k_scales", k_scales), ("v_scales", v_scales)):
+            if (t.dtype != torch.float32 or t.device != q.device or not t.is_contiguous() or t.dim() != 1
+                    or t.shape[0] < self.params.total_budget * self.params.n_kv_heads):
+                raise ValueError(f"{name}: expected a contiguous float32 vector with one entry per cache row on {q.device}")
         stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         _check(load_library().meda_decode_attention_fp8(
             ctypes.byref(self.params), _ptr(q), _ptr(k_codes), _ptr(v_codes), _ptr(k_scales), _ptr(v_scales),
@@ -290,6 +322,7 @@ class Decoder:
         return self.out
 
     def __call__(self, q, k_cache, v_cache, layer_len, layer_off, k_new=None, v_new=None, stream=None):
+        _check_decode_tensors(self.params, q, k_cache, v_cache, q.dtype, layer_len, layer_off, k_new, v_new)
         stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         _check(load_library().meda_decode_attention(
             ctypes.byref(self.params), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(layer_len), _ptr(layer_off),
@@ -302,6 +335,7 @@ def meda_decode_attention_noalloc(params: MedaDecodeParams, q, k_cache, v_cache,
                                   k_new=None, v_new=None, stream=None):
     """meda_decode_attention without a workspace: the library's built-in device array holds the chunk partials.
     ``out`` [L][Hq][d] is written in place (the call itself allocates nothing)."""
+    _check_decode_tensors(params, q, k_cache, v_cache, q.dtype, layer_len, layer_off, k_new, v_new, out)
     stream = stream if stream is not None else torch.cuda.current_stream(q.device)
     _check(load_library().meda_decode_attention_noalloc(
         ctypes.byref(params), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(layer_len), _ptr(layer_off),

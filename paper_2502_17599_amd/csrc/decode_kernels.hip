@@ -589,11 +589,12 @@ static meda_status make_decode_plan(const meda_decode_params* p, DecodePlan* pl)
   if (p->n_layers < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1 || p->n_new < 0) return MEDA_ERR_INVALID_ARG;
   if (p->n_q_heads % p->n_kv_heads != 0) return MEDA_ERR_INVALID_ARG;
   if (p->total_budget < p->n_layers) return MEDA_ERR_BUDGET;  // every layer keeps at least one row
-  if (!(p->softmax_scale >= 0.0f)) return MEDA_ERR_INVALID_ARG;
+  if (!(p->softmax_scale >= 0.0f) || !isfinite(p->softmax_scale)) return MEDA_ERR_INVALID_ARG;
   if (p->dtype != MEDA_F32 && p->dtype != MEDA_BF16) return MEDA_ERR_UNSUPPORTED;
   if (p->head_dim != 64 && p->head_dim != 128) return MEDA_ERR_UNSUPPORTED;
   const int G = p->n_q_heads / p->n_kv_heads;
   if (G > 8 || p->n_layers > 65535 || p->n_kv_heads > 65535) return MEDA_ERR_UNSUPPORTED;
+  if ((int64_t)p->n_layers * p->n_q_heads >= (1ll << 24)) return MEDA_ERR_UNSUPPORTED;  // (layer, head) ids are ints
   pl->L = p->n_layers; pl->Hq = p->n_q_heads; pl->Hkv = p->n_kv_heads; pl->G = G; pl->d = p->head_dim;
   pl->GP = G <= 1 ? 1 : (G <= 2 ? 2 : (G <= 4 ? 4 : 8));
   pl->dtype = p->dtype; pl->n_new = p->n_new;

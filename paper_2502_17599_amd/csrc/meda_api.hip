@@ -63,7 +63,14 @@ meda_status make_plan(const meda_params* p, Plan* out) {
   const int64_t layers = (int64_t)n_seqs * p->n_layers;  // layers of the whole batch
   if (layers > kMaxLayers) return MEDA_ERR_UNSUPPORTED;
   if (layers * p->n_kv_heads * (int64_t)p->seq_len >= (1ll << 31)) return MEDA_ERR_UNSUPPORTED;
-  if (layers * p->n_q_heads * 128 >= (1ll << 31)) return MEDA_ERR_UNSUPPORTED;
+  {
+    // row statistics are indexed with 32 bits over [layers][Hq][scoring rows, at least one padded window of 128];
+    // offsets inside one (layer, head) of q, k, v are 32-bit byte counts
+    const int64_t rows = (p->flags & MEDA_FLAG_FULL_PROMPT) ? p->seq_len : p->window;
+    if (layers * p->n_q_heads * (rows > 128 ? rows : 128) >= (1ll << 31)) return MEDA_ERR_UNSUPPORTED;
+    const int64_t elt = (p->dtype == MEDA_BF16) ? 2 : 4;
+    if ((int64_t)p->seq_len * p->head_dim * elt >= (1ll << 31)) return MEDA_ERR_UNSUPPORTED;
+  }
   {
     const int64_t lo1 = (int64_t)p->n_layers * (p->window < p->seq_len ? p->window : p->seq_len);
     if (p->total_budget < lo1 || p->total_budget > (int64_t)p->n_layers * p->seq_len) return MEDA_ERR_BUDGET;

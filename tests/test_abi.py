@@ -52,6 +52,15 @@ def test_workspace_bytes_valid_and_invalid(lib):
     # observation windows of more than 128 rows take the row-block mode of the scoring kernels
     assert pkg.meda_workspace_bytes(_params(window=129, seq_len=4096, total_budget=4 * 500)) > 0
     assert pkg.meda_workspace_bytes(_params(window=1000, total_budget=4 * 1000)) > 0
+    # sizes whose 32-bit offsets would wrap are refused: a row of one (layer, head) must start below 2 GiB, and the
+    # row statistics of all (layer, head, scoring row) triples are counted with 32 bits
+    big = dict(n_layers=1, n_q_heads=1, n_kv_heads=1, window=32)
+    assert pkg.meda_workspace_bytes(_params(seq_len=(1 << 23) - 1, total_budget=1 << 22, **big)) > 0
+    assert pkg.meda_workspace_bytes(_params(seq_len=1 << 23, total_budget=1 << 22, **big)) == 0
+    assert pkg.meda_workspace_bytes(_params(seq_len=1 << 22, total_budget=1 << 21, dtype=torch.float32, **big)) == 0
+    wide = dict(n_layers=32, n_q_heads=64, n_kv_heads=2, seq_len=1 << 20, total_budget=32 << 19, flags=4)
+    assert pkg.meda_workspace_bytes(_params(**wide)) == 0                       # 32 * 64 * 2^20 rows of statistics
+    assert pkg.meda_workspace_bytes(_params(**dict(wide, flags=0))) > 0         # 128 rows per head without the flag
     # a batch: the workspace grows with the number of sequences (64 x 4 layers is the largest batch of this shape)
     one, four = pkg.meda_workspace_bytes(_params()), pkg.meda_workspace_bytes(_params(n_seqs=4))
     assert pkg.meda_workspace_bytes(_params(n_seqs=1)) == one and 3 * one < four <= 4 * one + 4096
@@ -123,7 +132,8 @@ def test_decode_workspace_and_argument_checks(lib):
     assert need > 0 and need % 256 == 0
     assert ctypes.sizeof(pkg.MedaDecodeParams) == 40 and pkg.MedaDecodeParams.total_budget.offset == 24
     for bad in (dict(n_layers=0), dict(n_q_heads=7), dict(head_dim=96), dict(n_new=-1), dict(total_budget=3),
-                dict(n_q_heads=18, n_kv_heads=2), dict(dtype=5)):
+                dict(n_q_heads=18, n_kv_heads=2), dict(dtype=5), dict(softmax_scale=float("inf")),
+                dict(n_layers=60000, n_q_heads=512, n_kv_heads=64, total_budget=60000)):
         kw = dict(n_layers=4, n_q_heads=8, n_kv_heads=2, head_dim=128, total_budget=1000, dtype=torch.bfloat16)
         kw.update(bad)
         assert pkg.meda_decode_workspace_bytes(pkg.make_decode_params(**kw)) == 0, bad

@@ -152,6 +152,18 @@ def test_fp8_decode_needs_bf16_queries():
     import paper_2502_17599_amd as pkg
     params = pkg.make_decode_params(2, 4, 4, 128, 64, torch.float32)
     dec = pkg.Decoder(params, torch.device(DEV))
-    z = torch.zeros(16, device=DEV)
-    with pytest.raises(pkg.MedaError):
-        dec.fp8(z, z, z, z, z, z, z)
+    q = torch.zeros(2, 4, 128, device=DEV)
+    codes = torch.zeros(64 * 4, 128, dtype=torch.uint8, device=DEV)
+    scales = torch.ones(64 * 4, device=DEV)
+    lens = torch.full((2,), 32, dtype=torch.int32, device=DEV)
+    offs = torch.tensor([0, 32, 64], dtype=torch.int64, device=DEV)
+    with pytest.raises(pkg.MedaError) as ei:
+        dec.fp8(q, codes, codes, scales, scales, lens, offs)
+    assert ei.value.status == 3
+    # the binding checks shapes, types and placement before the library sees the pointers
+    with pytest.raises(ValueError):
+        dec(q, codes, codes, lens, offs)                      # cache rows of another type than q
+    with pytest.raises(ValueError):
+        dec(q, q.new_zeros(100, 128), q.new_zeros(100, 128), lens, offs)   # fewer rows than the budget
+    with pytest.raises(ValueError):
+        dec(q, q.new_zeros(256, 128), q.new_zeros(256, 128), lens.long(), offs)

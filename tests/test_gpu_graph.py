@@ -20,7 +20,7 @@ def test_graph_replays_equal_eager_results():
     params = pkg.make_params(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.seq_len, wl.window,
                              wl.total_budget, q.dtype, wl.recent_num, wl.recent_den)
     comp = pkg.Compressor(params, dev, want_merge_assign=True)
-    dq = torch.randn(wl.n_layers, wl.n_q_heads, wl.head_dim, generator=torch.Generator().manual_seed(3)).to(dev)
+    dq = torch.randn(wl.n_layers, wl.n_q_heads, wl.head_dim, generator=torch.Generator().manual_seed(3)).to(q.dtype).to(dev)
     dec = pkg.Decoder(pkg.make_decode_params(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.total_budget,
                                              q.dtype), dev)
     pkg.meda_profile_enable(False)

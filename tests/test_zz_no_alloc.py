@@ -68,8 +68,11 @@ def test_no_alloc_rejects_what_does_not_fit():
     dev = torch.device("cuda:0")
     dummy = torch.zeros(4096, dtype=torch.uint8, device=dev)
     out = torch.zeros(128, 64, 128, dtype=torch.bfloat16, device=dev)
-    with pytest.raises(pkg.MedaError) as ei:
-        pkg.meda_decode_attention_noalloc(dparams, dummy, dummy, dummy, dummy, dummy, out)
-    assert ei.value.status == 6
+    # through the library itself (the binding would first ask for a cache of 10^8 rows): the data pointers are never read
+    import ctypes
+    ptr = ctypes.c_void_p(dummy.data_ptr())
+    st = pkg.load_library().meda_decode_attention_noalloc(ctypes.byref(dparams), ptr, ptr, ptr, ptr, ptr, None, None,
+                                                          ctypes.c_void_p(out.data_ptr()), None)
+    assert st == 6 and "scratch" in pkg.meda_status_string(st)
     torch.cuda.synchronize()
     assert float(out.abs().max()) == 0.0
