@@ -355,19 +355,23 @@ __global__ void __launch_bounds__(kResThreads, 2) similarity_resident_kernel(Mer
   const int S_pad = (S + 31) & ~31;
   char* ckeys = smem;
   float* cinv = reinterpret_cast<float*>(smem + (size_t)S_pad * TL::kStride);
+  // Pieces past the end repeat the last piece, for the load and for the store (the same bytes to the same place),
+  // so the loop body has no branch: with a test around each store the compiler kept the batch in scratch memory
+  // and fetched the later pieces one by one, each behind a full wait.
   constexpr int kBatch = 6;  // pieces per thread whose loads are in flight together
   const int n_pieces = S_pad * CPR;
   for (int p0 = tid; p0 < n_pieces; p0 += kBatch * kResThreads) {
-    uint4 v[kBatch];
+    typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+    u32x4_t v[kBatch];
 #pragma unroll
     for (int i = 0; i < kBatch; ++i) {
       const int p = min(p0 + i * kResThreads, n_pieces - 1);
-      v[i] = *reinterpret_cast<const uint4*>(pk + (unsigned)(min(p / CPR, S - 1) * TL::kRowBytes + (p % CPR) * 16));
+      v[i] = *reinterpret_cast<const u32x4_t*>(pk + (unsigned)(min(p / CPR, S - 1) * TL::kRowBytes + (p % CPR) * 16));
     }
 #pragma unroll
     for (int i = 0; i < kBatch; ++i) {
-      const int p = p0 + i * kResThreads;
-      if (p < n_pieces) *reinterpret_cast<uint4*>(ckeys + (p / CPR) * TL::kStride + (p % CPR) * 16) = v[i];
+      const int p = min(p0 + i * kResThreads, n_pieces - 1);
+      *reinterpret_cast<u32x4_t*>(ckeys + (p / CPR) * TL::kStride + (p % CPR) * 16) = v[i];
     }
   }
   for (int sl = tid; sl < S_pad; sl += kResThreads) cinv[sl] = sinv[min(sl, S - 1)];
