@@ -346,32 +346,45 @@ __global__ void __launch_bounds__(kResThreads, 2) similarity_resident_kernel(Mer
   int lrow[2], nrow[2];
   chunk_rows(c, lrow);
   chunk_rows(c + kChunkStep, nrow);
+  // k-step i of a fragment takes the bytes [32 i + 16 kg, + 16) of its row: the two lane groups read adjacent
+  // pieces, so a load instruction touches 32 cache lines instead of the 64 of the half-row mapping (this kernel
+  // loads 64 rows per wave and chunk, all the time).  The conserved keys are read from LDS with the same mapping,
+  // and any fixed order of the k-steps gives the same products.
+  auto row_frag = [&](Frag<T, D>& f, const char* row_ptr) {
+#pragma unroll
+    for (int i = 0; i < TL::kFragChunks; ++i) f.c[i] = *reinterpret_cast<const uint4*>(row_ptr + i * 32 + kg * 16);
+  };
   Frag<T, D> lf[2];
 #pragma unroll
-  for (int s = 0; s < 2; ++s) frag_load(lf[s], kbase + (size_t)lrow[s] * TL::kRowBytes, kg);
+  for (int s = 0; s < 2; ++s) row_frag(lf[s], kbase + (size_t)lrow[s] * TL::kRowBytes);
 
   // Prologue: the conserved keys into LDS.  The set is padded to a multiple of 32 slots with
   // copies of the last key (a copy can never win a tie against the original, see sim_block_simple).
   const int S_pad = (S + 31) & ~31;
   char* ckeys = smem;
   float* cinv = reinterpret_cast<float*>(smem + (size_t)S_pad * TL::kStride);
-  // Pieces past the end repeat the last piece, for the load and for the store (the same bytes to the same place),
-  // so the loop body has no branch: with a test around each store the compiler kept the batch in scratch memory
-  // and fetched the later pieces one by one, each behind a full wait.
-  constexpr int kBatch = 6;  // pieces per thread whose loads are in flight together
+  // All pieces of the set are requested before the first one is stored (one memory latency for the whole set; at
+  // most kMaxPieces 16-byte pieces per thread; the bounds are the same for every thread of the workgroup, so the
+  // tests are scalar branches).  The batch is an array of a native vector type: as an array of uint4 the compiler
+  // kept it in scratch memory.
+  constexpr int kMaxPieces = (resident_capacity<T, D>() * CPR + kResThreads - 1) / kResThreads;
   const int n_pieces = S_pad * CPR;
-  for (int p0 = tid; p0 < n_pieces; p0 += kBatch * kResThreads) {
+  {
     typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
-    u32x4_t v[kBatch];
+    u32x4_t v[kMaxPieces > 0 ? kMaxPieces : 1];
 #pragma unroll
-    for (int i = 0; i < kBatch; ++i) {
-      const int p = min(p0 + i * kResThreads, n_pieces - 1);
-      v[i] = *reinterpret_cast<const u32x4_t*>(pk + (unsigned)(min(p / CPR, S - 1) * TL::kRowBytes + (p % CPR) * 16));
+    for (int i = 0; i < kMaxPieces; ++i) {
+      if (i * kResThreads < n_pieces) {
+        const int p = min(tid + i * kResThreads, n_pieces - 1);
+        v[i] = *reinterpret_cast<const u32x4_t*>(pk + (unsigned)(min(p / CPR, S - 1) * TL::kRowBytes + (p % CPR) * 16));
+      }
     }
 #pragma unroll
-    for (int i = 0; i < kBatch; ++i) {
-      const int p = min(p0 + i * kResThreads, n_pieces - 1);
-      *reinterpret_cast<u32x4_t*>(ckeys + (p / CPR) * TL::kStride + (p % CPR) * 16) = v[i];
+    for (int i = 0; i < kMaxPieces; ++i) {
+      if (i * kResThreads < n_pieces) {
+        const int p = min(tid + i * kResThreads, n_pieces - 1);  // a repeated piece: the same bytes to the same place
+        *reinterpret_cast<u32x4_t*>(ckeys + (p / CPR) * TL::kStride + (p % CPR) * 16) = v[i];
+      }
     }
   }
   for (int sl = tid; sl < S_pad; sl += kResThreads) cinv[sl] = sinv[min(sl, S - 1)];
@@ -380,7 +393,7 @@ __global__ void __launch_bounds__(kResThreads, 2) similarity_resident_kernel(Mer
   const int nblocks = S_pad / 32;
   unsigned coff[TL::kFragChunks];   // chunk c of this lane's fragment inside a block of 32 padded rows
 #pragma unroll
-  for (int c = 0; c < TL::kFragChunks; ++c) coff[c] = (unsigned)(n * TL::kStride + kg * TL::kHalfBytes + c * 16);
+  for (int c = 0; c < TL::kFragChunks; ++c) coff[c] = (unsigned)(n * TL::kStride + c * 32 + kg * 16);
   auto block_base = [&](int b) { return ckeys + b * 32 * TL::kStride; };
   auto block_inv = [&](int b) { return cinv + b * 32 + kg * 4; };
   while (c < n_chunks) {
@@ -389,7 +402,7 @@ __global__ void __launch_bounds__(kResThreads, 2) similarity_resident_kernel(Mer
     const int r0 = c * kSimRowsPerWave;
     Frag<T, D> lfn[2];
 #pragma unroll
-    for (int s = 0; s < 2; ++s) frag_load(lfn[s], kbase + (size_t)nrow[s] * TL::kRowBytes, kg);
+    for (int s = 0; s < 2; ++s) row_frag(lfn[s], kbase + (size_t)nrow[s] * TL::kRowBytes);
     int nnrow[2];
     chunk_rows(c + 2 * kChunkStep, nnrow);
     RowBest rb[2];
