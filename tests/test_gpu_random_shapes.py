@@ -163,3 +163,37 @@ def test_random_shape_with_flags(wl, flags):
             ma = gpu["merge_assign"][l, g]
             assert np.array_equal(ma[idx], np.arange(len(idx)))
             assert np.all(ma[np.setdiff1d(np.arange(T), idx)] == -1)
+
+
+def _many_pairs_configs():
+    """At least 256 (layer, kv head) pairs, which is when the similarity search sends layers whose conserved set fits
+    into LDS to its resident-set kernel; average budgets on both sides of that capacity (576 rows of 256 bytes, 1184
+    rows of 128 bytes), so that most cases run both kernels."""
+    r = np.random.Generator(np.random.Philox(key=[2024, 9]))
+    out = []
+    for i in range(6):
+        L, hkv = [(8, 32), (16, 16), (32, 8), (64, 4), (16, 32), (64, 8)][i]
+        G = int(r.choice([1, 2, 4]))
+        T = int(r.choice([640, 1000, 1537, 2048]))
+        W = int(r.choice([8, 32, 64]))
+        d = (64, 128)[i % 2]
+        dtype = ("bf16", "bf16", "f32")[i % 3]
+        avg = int(r.choice([100, 300, 560, 600, 1000]))
+        B = int(max(L * W, L * min(avg, 3 * T // 4)))
+        out.append(variant(TINY, name=f"pairs{i}", n_layers=L, n_q_heads=hkv * G, n_kv_heads=hkv, head_dim=d, dtype=dtype,
+                           layout=_random_layout(r, T), window=W, total_budget=B, seed=400 + i, tau_lo=0.3, tau_hi=3.0,
+                           heavy_frac=float(r.choice([0.0, 0.02]))))
+    return out
+
+
+@pytest.mark.parametrize("wl", _many_pairs_configs(), ids=lambda w: w.name)
+def test_random_shape_with_many_layer_head_pairs(wl):
+    print(f"\n[many-pairs case] {wl.name}: L={wl.n_layers} Hq={wl.n_q_heads} Hkv={wl.n_kv_heads} d={wl.head_dim} "
+          f"T={wl.seq_len} W={wl.window} B={wl.total_budget} {wl.dtype}", flush=True)
+    data = generate(wl)
+    comp, gpu = run_gpu(wl, data)
+    order = np.argsort(gpu["S"])
+    layers = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2]), int(order[len(order) // 3])})
+    # entropies and budgets of all layers; selection, matching and merged rows of one head of the layers with the
+    # smallest, the largest and two middle budgets
+    check_all(wl, data, gpu, heads=[(l, (l * 7) % wl.n_kv_heads) for l in layers], threads=8)
