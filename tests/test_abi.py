@@ -172,3 +172,16 @@ def test_fp8_entry_points_validate_on_the_host(lib):
     assert f(ctypes.byref(p32), a, a, a, a, a, a, a, None, None, a, a, 1 << 30, None) == 3
     assert f(ctypes.byref(p16), a, a, a, None, a, a, a, None, None, a, a, 1 << 30, None) == 1
     assert f(ctypes.byref(p16), a, a, a, a, a, a, a, None, None, a, a, 16, None) == 4            # workspace too small
+
+
+def test_decode_binding_checks_tensors_before_the_library_sees_pointers():
+    # shapes, types and placement are checked in the binding (the C entry points take plain pointers); without a GPU
+    # the first check, placement, is the one that can be exercised
+    from paper_2502_17599_amd import _lib
+    p = pkg.make_decode_params(2, 4, 2, 64, 2 * 10, torch.float32)
+    q = torch.zeros(2, 4, 64)
+    rows = torch.zeros(2 * 10 * 2, 64)
+    lens = torch.full((2,), 10, dtype=torch.int32)
+    offs = torch.tensor([0, 10, 20], dtype=torch.int64)
+    with pytest.raises(ValueError, match="on the GPU"):
+        _lib._check_decode_tensors(p, q, rows, rows, torch.float32, lens, offs, None, None)
