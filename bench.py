@@ -241,13 +241,27 @@ def measured_peaks(pkg, torch, dev):
     ms_mfma = median_ms(mfma(False))
     ms_mfma_rnd = median_ms(mfma(True))
     del buf
+    # vector work beside the matrix instructions: nanoseconds per round of 16 matrix instructions and 16 V
+    # multiply-adds per wave, written between the matrix instructions or as a phase after them
+    rounds = 20000
+    beside = {}
+    for waves in (1, 2):
+        for inter in (True, False):
+            for v in (0, 4, 6, 8):
+                if v == 0 and not inter:
+                    continue
+                ms = median_ms(lambda: pkg.meda_peak_mfma_valu(rounds, v, inter, waves, sink), n=3)
+                beside[f"{waves}w_{'interleaved' if inter else 'phased'}_V{v}"] = round(ms * 1e6 / rounds, 1)
     return {"hbm_read_GBps": (2 << 30) / (ms_read * 1e-3) / 1e9,
+            "mfma_with_valu_ns_per_round": beside,
             "bf16_mfma_TFLOPs": total[0] * 32768.0 / (ms_mfma * 1e-3) / 1e12,
             # the same instruction stream on operands whose bits toggle: the power-limited rate real data allows
             "bf16_mfma_random_operands_TFLOPs": total[0] * 32768.0 / (ms_mfma_rnd * 1e-3) / 1e12,
             "published": {"hbm_GBps": HBM_PEAK_GBS, "bf16_mfma_TFLOPs": MFMA_PEAK_TFLOPS["bf16"]},
             "how": "meda_peak_stream_read over 2 GiB; meda_peak_mfma_bf16, 131072 32x32x16 instructions per wave, "
-                   "2 waves per SIMD, nearly constant and pseudo-random operands; median of 5 launches"}
+                   "2 waves per SIMD, nearly constant and pseudo-random operands; median of 5 launches; "
+                   "meda_peak_mfma_valu, 20000 rounds of 16 matrix instructions + 16 V multiply-adds per wave, "
+                   "1 or 2 waves per SIMD, median of 3 launches"}
 
 
 def _cpu_info():

@@ -243,11 +243,21 @@ meda_status meda_decode_attention_fp8(const meda_decode_params* params, const vo
  *                           random_operands = 0: operands nearly constant; 1: pseudo-random signs and mantissas
  *                           (more bits toggle per step, the chip draws more power and holds a lower clock: the
  *                           rate a kernel working on real data can hope for).
+ *   meda_peak_mfma_valu     how much vector work fits beside the matrix instructions: every wave runs `rounds`
+ *                           (1 .. 2^22) rounds of 16 bf16 32x32x16 matrix instructions (two accumulator chains,
+ *                           nearly constant operands) and 16 * valu_per_mfma (0, 4, 6 or 8) independent fp32
+ *                           multiply-adds, written right behind each matrix instruction (interleaved != 0) or all
+ *                           after the sixteenth (a matrix phase, then a vector phase); waves_per_simd (1 or 2)
+ *                           workgroups of one wave per SIMD run on every CU.  Time per round against the run with
+ *                           valu_per_mfma = 0 tells what the vector work costs.  MEDA_ERR_INVALID_ARG for other
+ *                           values.
  * `sink` is a 4-byte aligned device word that is never actually written (it keeps the work alive).
  */
 meda_status meda_peak_stream_read(const void* src, size_t bytes, void* sink, void* hip_stream);
 meda_status meda_peak_mfma_bf16(int64_t mfma_per_wave, int32_t random_operands, int64_t* total_mfma, void* sink,
                                 void* hip_stream);
+meda_status meda_peak_mfma_valu(int64_t rounds, int32_t valu_per_mfma, int32_t interleaved, int32_t waves_per_simd,
+                                void* sink, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -15,7 +15,7 @@ EXPORTED_SYMBOLS = ("meda_workspace_bytes", "meda_compress", "meda_workspace_reg
                     "meda_profile_enable", "meda_profile_read", "meda_phase_name", "meda_status_string",
                     "meda_decode_workspace_bytes", "meda_decode_attention",
                     "meda_quantize_fp8", "meda_dequantize_fp8", "meda_decode_attention_fp8",
-                    "meda_decode_attention_noalloc", "meda_peak_stream_read", "meda_peak_mfma_bf16")
+                    "meda_decode_attention_noalloc", "meda_peak_stream_read", "meda_peak_mfma_bf16", "meda_peak_mfma_valu")
 DECODE_NOALLOC_MAX_BYTES = 40 << 20
 REGIONS = {"col_scores": 0, "inv_norm": 1, "row_stats": 2, "alloc": 3, "less_idx": 4, "less_slot": 5}
 N_PHASES = 8
@@ -90,6 +90,8 @@ def load_library() -> ctypes.CDLL:
     lib.meda_peak_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     lib.meda_peak_mfma_bf16.restype = ctypes.c_int
     lib.meda_peak_mfma_bf16.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64), vp, vp]
+    lib.meda_peak_mfma_valu.restype = ctypes.c_int
+    lib.meda_peak_mfma_valu.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.meda_quantize_fp8.restype = ctypes.c_int
     lib.meda_quantize_fp8.argtypes = [vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, vp, vp, vp]
     lib.meda_dequantize_fp8.restype = ctypes.c_int
@@ -357,6 +359,15 @@ def meda_peak_mfma_bf16(mfma_per_wave: int, sink: torch.Tensor, random_operands:
     _check(load_library().meda_peak_mfma_bf16(int(mfma_per_wave), 1 if random_operands else 0, ctypes.byref(total), _ptr(sink),
                                               ctypes.c_void_p(stream.cuda_stream)))
     return int(total.value)
+
+
+def meda_peak_mfma_valu(rounds: int, valu_per_mfma: int, interleaved: bool, waves_per_simd: int, sink: torch.Tensor,
+                        stream=None) -> None:
+    """Enqueue the matrix-plus-vector micro-kernel (measurement aid): 16 matrix instructions and 16 * valu_per_mfma
+    multiply-adds per round and wave."""
+    stream = stream if stream is not None else torch.cuda.current_stream(sink.device)
+    _check(load_library().meda_peak_mfma_valu(int(rounds), int(valu_per_mfma), 1 if interleaved else 0, int(waves_per_simd),
+                                              _ptr(sink), ctypes.c_void_p(stream.cuda_stream)))
 
 
 def meda_quantize_fp8(rows: torch.Tensor, stream=None):

@@ -79,6 +79,66 @@ __global__ void __launch_bounds__(kPeakThreads, 2) peak_mfma_bf16_kernel(long lo
   if (s == -1.0f) *sink = s;
 }
 
+// How much vector work fits beside the matrix instructions: every round issues 16 matrix instructions (two
+// accumulator chains) and 16 * V independent fp32 multiply-adds on private registers, the multiply-adds either
+// right behind each matrix instruction (INTERLEAVED; the order is pinned with a scheduling barrier per pair of
+// matrix instructions) or all after the sixteenth (a matrix phase and a vector phase, as a kernel has them whose
+// vector work depends on the products).  Nearly constant operands, no memory.  The multiply-adds are volatile asm
+// so that they are neither merged nor moved.
+template <int V, bool INTERLEAVED>
+__global__ void __launch_bounds__(kPeakThreads, 2) peak_mfma_valu_kernel(long long rounds, float* sink) {
+  const uint32_t seed = 0x3f803f80u + (threadIdx.x & 7u);
+  const uint4 a4 = make_uint4(seed, seed ^ 0x00010000u, seed, seed ^ 0x00000001u);
+  const uint4 b4 = make_uint4(seed ^ 0x00020002u, seed, seed ^ 0x00010001u, seed);
+  const bf16x8_t a = __builtin_bit_cast(bf16x8_t, a4), b = __builtin_bit_cast(bf16x8_t, b4);
+  f32x16_t c0 = acc_zero(), c1 = acc_zero();
+  float x[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) x[i] = 1.0f + threadIdx.x * 1e-3f + i;
+  const float m = 0.999f, d = 1e-3f;  // x stays bounded: x <- 0.999 x + 0.001
+  for (long long r = 0; r < rounds; ++r) {
+    if constexpr (INTERLEAVED) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < V; ++j) asm volatile("v_fma_f32 %0, %0, %1, %2" : "+v"(x[j & 7]) : "v"(m), "v"(d));
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, c1, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < V; ++j) asm volatile("v_fma_f32 %0, %0, %1, %2" : "+v"(x[(j + 4) & 7]) : "v"(m), "v"(d));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, c1, 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < 16 * V; ++j) asm volatile("v_fma_f32 %0, %0, %1, %2" : "+v"(x[j & 7]) : "v"(m), "v"(d));
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s += c0[i] + c1[i];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) s += x[i];
+  if (s == -1.0f) *sink = s;
+}
+
+template <bool INTERLEAVED>
+static bool launch_mfma_valu(int v, unsigned blocks, long long rounds, float* sink, hipStream_t s) {
+  switch (v) {
+    case 0: hipLaunchKernelGGL((peak_mfma_valu_kernel<0, INTERLEAVED>), dim3(blocks), dim3(kPeakThreads), 0, s, rounds, sink); return true;
+    case 4: hipLaunchKernelGGL((peak_mfma_valu_kernel<4, INTERLEAVED>), dim3(blocks), dim3(kPeakThreads), 0, s, rounds, sink); return true;
+    case 6: hipLaunchKernelGGL((peak_mfma_valu_kernel<6, INTERLEAVED>), dim3(blocks), dim3(kPeakThreads), 0, s, rounds, sink); return true;
+    case 8: hipLaunchKernelGGL((peak_mfma_valu_kernel<8, INTERLEAVED>), dim3(blocks), dim3(kPeakThreads), 0, s, rounds, sink); return true;
+    default: return false;
+  }
+}
+
 }  // namespace meda
 
 extern "C" {
@@ -112,6 +172,23 @@ meda_status meda_peak_mfma_bf16(int64_t mfma_per_wave, int32_t random_operands, 
   if (hipGetLastError() != hipSuccess) return MEDA_ERR_HIP;
   *total_mfma = (int64_t)rounds * 16 * (meda::kPeakThreads / 64) * blocks;
   return MEDA_OK;
+}
+
+meda_status meda_peak_mfma_valu(int64_t rounds, int32_t valu_per_mfma, int32_t interleaved, int32_t waves_per_simd,
+                                void* sink, void* hip_stream) {
+  if (rounds < 1 || rounds > (1ll << 22) || !sink || ((uintptr_t)sink & 3u)) return MEDA_ERR_INVALID_ARG;
+  if (valu_per_mfma != 0 && valu_per_mfma != 4 && valu_per_mfma != 6 && valu_per_mfma != 8) return MEDA_ERR_INVALID_ARG;
+  if (waves_per_simd != 1 && waves_per_simd != 2) return MEDA_ERR_INVALID_ARG;
+  int dev = 0, cus = 256;
+  if (hipGetDevice(&dev) != hipSuccess) return MEDA_ERR_HIP;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return MEDA_ERR_HIP;
+  const unsigned blocks = (unsigned)cus * (unsigned)waves_per_simd;  // a workgroup is one wave on every SIMD of a CU
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  float* snk = static_cast<float*>(sink);
+  const bool ok = interleaved ? meda::launch_mfma_valu<true>(valu_per_mfma, blocks, rounds, snk, s)
+                              : meda::launch_mfma_valu<false>(valu_per_mfma, blocks, rounds, snk, s);
+  if (!ok) return MEDA_ERR_INVALID_ARG;
+  return hipGetLastError() == hipSuccess ? MEDA_OK : MEDA_ERR_HIP;
 }
 
 }  // extern "C"

@@ -185,3 +185,11 @@ def test_decode_binding_checks_tensors_before_the_library_sees_pointers():
     offs = torch.tensor([0, 10, 20], dtype=torch.int64)
     with pytest.raises(ValueError, match="on the GPU"):
         _lib._check_decode_tensors(p, q, rows, rows, torch.float32, lens, offs, None, None)
+
+
+def test_peak_probe_validates_its_arguments_on_the_host(lib):
+    fake = ctypes.c_void_p(0x10000)  # never dereferenced: every call below fails validation
+    for rounds, v, inter, waves, sink in ((0, 4, 1, 1, fake), (1 << 23, 4, 1, 1, fake), (100, 5, 1, 1, fake),
+                                          (100, 4, 1, 3, fake), (100, 4, 0, 0, fake), (100, 4, 1, 1, None),
+                                          (100, 4, 1, 1, ctypes.c_void_p(0x10002))):
+        assert lib.meda_peak_mfma_valu(rounds, v, inter, waves, sink, None) == 1, (rounds, v, inter, waves)
