@@ -227,8 +227,10 @@ __global__ void __launch_bounds__(kSimWaves * 64, (Tile<T, D>::kRowBytes <= 256 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const long long off_l = a.off[l];
   const size_t cbase = (size_t)off_l * a.Hkv + (size_t)g * S;
-  const float* sinv = a.sel_inv_norm + cbase;
-  const char* pk = a.packed_k + cbase * TL::kRowBytes;  // this pair's conserved keys, contiguous
+  // the bases of the asynchronous copies below must sit in scalar registers: said explicitly, not left to what the
+  // compiler can prove about the address arithmetic
+  const float* sinv = uniform_ptr(a.sel_inv_norm + cbase);
+  const char* pk = uniform_ptr(a.packed_k + cbase * TL::kRowBytes);  // this pair's conserved keys, contiguous
   const size_t lbase = less_base_of(l, g, a.T, a.Hkv, off_l, S);
   const int32_t* less = a.less_idx + lbase;
   const char* kbase = a.k;  // positions are stored as row ids over all layers and heads
