@@ -146,6 +146,11 @@ def time_pass(pkg, torch, wl, dev, steps, warmup, flags=0, n_seqs=0, phase_event
         "pass_hbm_frac": (alg_bytes / (ms_per_step * 1e-3)) / (HBM_PEAK_GBS * 1e9),
         "pass_mfma_frac": ((work["similarity"] + score_flop) / (ms_per_step * 1e-3)) / (MFMA_PEAK_TFLOPS[wl.dtype] * 1e12),
         "phase_ms_warmup": per_phase,
+        # every phase against its own bound, from the warm-up times (every kernel bracketed by events, which adds a
+        # little to the short ones): algorithmic bytes or flops of a launch / time / published peak
+        "phase_frac_warmup": {n: {"bound": phase_bound[n], "frac": (work[n] / (per_phase[n] * 1e-3))
+                                  / (MFMA_PEAK_TFLOPS[wl.dtype] * 1e12 if phase_bound[n] == "mfma" else HBM_PEAK_GBS * 1e9)}
+                              for n in names if work.get(n) and per_phase[n] > 0},
         "roofline": roofline,
     }
     kept = (q, k, v, out, budgets[0]) if keep else None
@@ -432,7 +437,8 @@ def main():
                            "dtype": o["dtype"], "pass_hbm_frac": o["pass_hbm_frac"], "pass_mfma_frac": o["pass_mfma_frac"],
                            "dominant_kernel": o["roofline"]["kernel"], "dominant_bound": o["roofline"]["bound"],
                            "dominant_kernel_ms": o["roofline"]["kernel_ms"], "dominant_frac": o["roofline"]["frac"],
-                           "phase_ms_warmup": o["phase_ms_warmup"]})
+                           "phase_ms_warmup": o["phase_ms_warmup"],
+                           "phase_frac_warmup": {n: round(v["frac"], 4) for n, v in o["phase_frac_warmup"].items()}})
         rec["per_workload"] = others
     if not args.no_peaks:
         rec["measured_peak"] = measured_peaks(pkg, torch, dev)
