@@ -173,6 +173,7 @@ struct SelectArgs {
 };
 
 constexpr int kSelMaxThreads = 1024;
+constexpr int kSelBatch = 4;  // loads a thread has in flight in the counting passes
 constexpr int kSelMaxWaves = kSelMaxThreads / 64;
 
 // Exclusive rank of a one-bit flag over the workgroup (ballots inside a wave, wave totals in LDS).
@@ -190,6 +191,7 @@ __device__ __forceinline__ int flag_rank_in_wave(bool flag, int lane, int* wave_
 // fp32 scores (no bits are lost to the addition) with a 4 x 8-bit radix select on their bit
 // patterns (scores are >= 0, so the unsigned order of the bits is the order of the values); equal
 // scores go to the smaller position.
+template <int kSelItems>  // consecutive positions a thread takes per iteration of the output pass
 __global__ void __launch_bounds__(kSelMaxThreads) select_kernel(SelectArgs a) {
   __shared__ int hist[256];
   __shared__ int wtot[2][kSelMaxWaves];
@@ -209,9 +211,16 @@ __global__ void __launch_bounds__(kSelMaxThreads) select_kernel(SelectArgs a) {
   const size_t c_base = (size_t)off_l * a.Hkv + (size_t)g * S;
   const size_t less_base = ((size_t)l * T - (size_t)off_l) * a.Hkv + (size_t)g * (T - S);
 
-  // number of text candidates
+  // number of text candidates (kSelBatch loads in flight per thread: a pass over the scores of one head is bound by
+  // the latency of its loads, not by their bytes)
   int cnt = 0;
-  for (int j = tid; j < ncand; j += kSelThreads) cnt += (mask[j] == 0) ? 1 : 0;
+  for (int j0 = tid; j0 < ncand; j0 += kSelBatch * kSelThreads) {
+    uint8_t mk[kSelBatch];
+#pragma unroll
+    for (int i = 0; i < kSelBatch; ++i) mk[i] = mask[min(j0 + i * kSelThreads, ncand - 1)];
+#pragma unroll
+    for (int i = 0; i < kSelBatch; ++i) cnt += (j0 + i * kSelThreads < ncand && mk[i] == 0) ? 1 : 0;
+  }
   cnt = wave_sum(cnt);
   if (lane == 0) s_red[wave] = cnt;
   __syncthreads();
@@ -232,10 +241,19 @@ __global__ void __launch_bounds__(kSelMaxThreads) select_kernel(SelectArgs a) {
       if (tid < 256) hist[tid] = 0;
       __syncthreads();
       const unsigned prefix = s_prefix;
-      for (int j = tid; j < ncand; j += kSelThreads) {
-        if ((mask[j] != 0) == (cls != 0)) {
-          const unsigned key = __float_as_uint(scores[j]);
-          if ((key & prefix_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+      for (int j0 = tid; j0 < ncand; j0 += kSelBatch * kSelThreads) {
+        uint8_t mk[kSelBatch];
+        unsigned key[kSelBatch];
+#pragma unroll
+        for (int i = 0; i < kSelBatch; ++i) {
+          const int j = min(j0 + i * kSelThreads, ncand - 1);
+          mk[i] = mask[j];
+          key[i] = __float_as_uint(scores[j]);
+        }
+#pragma unroll
+        for (int i = 0; i < kSelBatch; ++i) {
+          if (j0 + i * kSelThreads < ncand && (mk[i] != 0) == (cls != 0) && (key[i] & prefix_mask) == prefix)
+            atomicAdd(&hist[(key[i] >> shift) & 255u], 1);
         }
       }
       __syncthreads();
@@ -273,48 +291,94 @@ __global__ void __launch_bounds__(kSelMaxThreads) select_kernel(SelectArgs a) {
     ties_taken = s_remaining;
   }
 
-  // ordered output: conserved positions ascending, the rest ascending
+  // ordered output: conserved positions ascending, the rest ascending.  A thread takes kSelItems consecutive
+  // positions per iteration (two barriers per kSelItems * blockDim positions); their mask, score and 1/|k| are
+  // requested one iteration ahead, so that the barriers do not sit behind the loads.
   int run_c = 0, run_tie = 0;
-  for (int base = 0; base < T; base += kSelThreads) {
-    const int j = base + tid;
-    const bool valid = j < T;
-    bool in_cls = false, is_tie = false, above = false;
-    if (valid && j < ncand) {
-      in_cls = (mask[j] != 0) == (cls != 0);
-      if (in_cls) {
-        const unsigned key = __float_as_uint(scores[j]);
-        above = key > threshold;
-        is_tie = key == threshold;
-      }
+  const unsigned long long lt_mask = (1ull << lane) - 1ull;
+  uint8_t mk_n[kSelItems];
+  unsigned key_n[kSelItems];
+  float inv_n[kSelItems];
+  auto fetch = [&](int j0) {
+#pragma unroll
+    for (int i = 0; i < kSelItems; ++i) {
+      const int jj = min(j0 + i, T - 1);
+      mk_n[i] = mask[jj];
+      key_n[i] = __float_as_uint(scores[jj]);
+      inv_n[i] = a.inv_norm[head_row0 + jj];
     }
-    int wt_tie, wt_sel;
-    const int tie_in_wave = flag_rank_in_wave(is_tie, lane, &wt_tie);
-    if (lane == 0) wtot[0][wave] = wt_tie;
+  };
+  fetch(tid * kSelItems);
+  for (int base = 0; base < T; base += kSelItems * kSelThreads) {
+    const int j0 = base + tid * kSelItems;
+    uint8_t mk[kSelItems];
+    unsigned key[kSelItems];
+    float inv[kSelItems];
+#pragma unroll
+    for (int i = 0; i < kSelItems; ++i) {
+      mk[i] = mk_n[i];
+      key[i] = key_n[i];
+      inv[i] = inv_n[i];
+    }
+    fetch(j0 + kSelItems * kSelThreads);
+    bool valid[kSelItems], in_cls[kSelItems], is_tie[kSelItems], above[kSelItems];
+    int tie_before = 0, tie_wave = 0;
+#pragma unroll
+    for (int i = 0; i < kSelItems; ++i) {
+      const int j = j0 + i;
+      valid[i] = j < T;
+      in_cls[i] = is_tie[i] = above[i] = false;
+      if (valid[i] && j < ncand) {
+        in_cls[i] = (mk[i] != 0) == (cls != 0);
+        if (in_cls[i]) {
+          above[i] = key[i] > threshold;
+          is_tie[i] = key[i] == threshold;
+        }
+      }
+      const unsigned long long b = __ballot(is_tie[i]);
+      tie_before += __popcll(b & lt_mask);  // ties at the positions of the lanes below
+      tie_wave += __popcll(b);
+    }
+    if (lane == 0) wtot[0][wave] = tie_wave;
     __syncthreads();
-    int tie_rank = run_tie + tie_in_wave, tie_total = 0;
+    int tie_rank = run_tie + tie_before, tie_total = 0;
     for (int i = 0; i < kSelWaves; ++i) {
       const int v = wtot[0][i];
       tie_rank += (i < wave) ? v : 0;
       tie_total += v;
     }
-    const bool sel = valid && (j >= ncand || (in_cls ? (above || (is_tie && tie_rank < ties_taken)) : other_taken));
-    const int sel_in_wave = flag_rank_in_wave(sel, lane, &wt_sel);
-    if (lane == 0) wtot[1][wave] = wt_sel;
+    bool sel[kSelItems];
+    int sel_before = 0, sel_wave = 0;
+#pragma unroll
+    for (int i = 0; i < kSelItems; ++i) {
+      const int j = j0 + i;
+      sel[i] = valid[i] && (j >= ncand || (in_cls[i] ? (above[i] || (is_tie[i] && tie_rank < ties_taken)) : other_taken));
+      tie_rank += is_tie[i] ? 1 : 0;  // this thread's positions are consecutive
+      const unsigned long long b = __ballot(sel[i]);
+      sel_before += __popcll(b & lt_mask);
+      sel_wave += __popcll(b);
+    }
+    if (lane == 0) wtot[1][wave] = sel_wave;
     __syncthreads();
-    int pos_c = run_c + sel_in_wave, sel_total = 0;
+    int pos_c = run_c + sel_before, sel_total = 0;
     for (int i = 0; i < kSelWaves; ++i) {
       const int v = wtot[1][i];
       pos_c += (i < wave) ? v : 0;
       sel_total += v;
     }
-    if (sel) {
-      a.sel_idx[c_base + pos_c] = head_row0 + j;
-      a.sel_inv_norm[c_base + pos_c] = a.inv_norm[head_row0 + j];
-      if (a.sel_idx_user) a.sel_idx_user[c_base + pos_c] = j;
-      if (a.merge_assign) a.merge_assign[head_row0 + j] = pos_c;
-    } else if (valid) {
-      a.less_idx[less_base + (j - pos_c)] = head_row0 + j;
-      if (a.merge_assign && a.no_merge) a.merge_assign[head_row0 + j] = -1;
+#pragma unroll
+    for (int i = 0; i < kSelItems; ++i) {
+      const int j = j0 + i;  // pos_c conserved positions lie before j
+      if (sel[i]) {
+        a.sel_idx[c_base + pos_c] = head_row0 + j;
+        a.sel_inv_norm[c_base + pos_c] = inv[i];
+        if (a.sel_idx_user) a.sel_idx_user[c_base + pos_c] = j;
+        if (a.merge_assign) a.merge_assign[head_row0 + j] = pos_c;
+        ++pos_c;
+      } else if (valid[i]) {
+        a.less_idx[less_base + (j - pos_c)] = head_row0 + j;
+        if (a.merge_assign && a.no_merge) a.merge_assign[head_row0 + j] = -1;
+      }
     }
     run_c += sel_total;
     run_tie += tie_total;
@@ -354,7 +418,10 @@ hipError_t launch_select(const Plan& p, const Buffers& b, hipStream_t s) {
   a.L = p.L; a.Hkv = p.Hkv; a.T = p.T; a.no_merge = (p.flags & MEDA_FLAG_NO_MERGE) ? 1 : 0;
   a.Lseq = p.Lseq;
   const int nthr = p.T >= 16384 ? 1024 : (p.T >= 4096 ? 512 : 256);
-  hipLaunchKernelGGL(select_kernel, dim3(p.Hkv, p.L), dim3(nthr), 0, s, a);
+  // long sequences: four positions per thread and iteration in the output pass (a quarter of the barriers); short
+  // ones have too few iterations for that to pay
+  if (p.T >= 16384) hipLaunchKernelGGL(select_kernel<4>, dim3(p.Hkv, p.L), dim3(nthr), 0, s, a);
+  else hipLaunchKernelGGL(select_kernel<1>, dim3(p.Hkv, p.L), dim3(nthr), 0, s, a);
   return hipGetLastError();
 }
 

@@ -250,3 +250,16 @@ def test_many_heads_small_context_both_similarity_kernels():
     print("budgets", S.tolist(), flush=True)
     assert (S <= 576).any() and (S > 576).any(), S
     check_all(wl, data, gpu, heads=[(l, g) for l in range(wl.n_layers) for g in (0, 13, 31)])
+
+
+def test_sequences_of_16384_positions_and_more_in_the_selection_kernel():
+    # from 16384 positions on, a thread of the selection kernel takes four consecutive positions per iteration of its
+    # output pass: a ragged length (the last thread's four positions straddle the end), a length that is a multiple of
+    # the 4096 positions of an iteration, identical heavy-hitter keys (exact score ties at the cut), a recent part
+    # that is not a multiple of four, text and vision candidates on both sides of the cut
+    layout = (("t", 100, -1), ("v", 9000, 0), ("t", 1200, -1), ("v", 6000, 1), ("t", 89, -1))      # 16389 positions
+    _case(variant(TINY, name="t16389", n_layers=2, n_q_heads=2, n_kv_heads=2, head_dim=64, dtype="f32", layout=layout,
+                  window=32, total_budget=2 * 2001, seed=61, heavy_frac=0.02), threads=8)
+    layout = (("v", 10000, 0), ("t", 300, -1), ("v", 10000, 1), ("t", 180, -1))                      # 20480 positions
+    _case(variant(TINY, name="t20480", n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=64, dtype="bf16", layout=layout,
+                  window=64, total_budget=2 * 333, seed=62, heavy_frac=0.02, recent_num=1, recent_den=3), threads=8)
