@@ -563,7 +563,7 @@ __global__ void __launch_bounds__(kSortMaxThreads, 8) segment_sort_kernel(MergeA
           if (lane < kSortDigits) wcnt[cur][wave][lane] = 0;
           if (valid && my_rank == 0) wcnt[cur][wave][dgt] = __popcll(peers);  // after the zeroing: same wave, in order
           __syncthreads();
-          if (wave == 0) {
+          if (wave == 0) {  // (a scan spread over all waves, 16 lanes per digit, measured slower than this walk by one wave)
             // lane (q, half): digit q = lane / 2, waves half*8 .. half*8+7; exclusive prefix over the waves
             const int q = lane >> 1, w0 = (lane & 1) * (kSortMaxWaves / 2);
             int run = 0, c[kSortMaxWaves / 2];
